@@ -1,0 +1,236 @@
+/*
+ * CPU oracle for attention over a paged KV cache with shared prefix blocks, and
+ * for the two block-copy operations.  TEST INFRASTRUCTURE ONLY: it is linked by
+ * nothing in the GPU library, and only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg load it.
+ *
+ * What it computes is the plain definition, in fp64, with no tiling, no
+ * awareness of sharing and no running softmax:
+ *
+ *   The paper (Sec. 2.4) describes inference as a prefill stage that projects
+ *   the input to Q, K, V and stores K and V in the cache, followed by decoding
+ *   that extends the cache one token at a time; prefix caching reuses the cached
+ *   blocks of an identical prefix while leaving outputs unchanged.  It never
+ *   writes the attention formula, so the textbook one is used: for query row i
+ *   of request r (new tokens occupy positions ctx .. ctx+q_len-1 with
+ *   ctx = seq_len - q_len), q head h with kv head h / (Hq/Hkv), and the
+ *   n = ctx + i + 1 visible keys j = 0..n-1 found through the request's own
+ *   block table,
+ *       s_j = scale * <q, k_j>,   w_j = exp(s_j - max s) / sum_j exp(s_j - max s),
+ *       out = sum_j w_j v_j.
+ *   n = 0 gives an all-zero row.
+ *
+ * Inputs are bf16 bit patterns, widened exactly to double.  Pool element
+ * (blk, p, hkv, t, c) is at ((((blk*2+p)*Hkv+hkv)*bs+t)*d+c), p = 0 K, 1 V.
+ *
+ * Every function here is pinned by tests that do not use this file's code:
+ * a pure-Python fsum brute force on 1-4 token cases, closed forms (uniform
+ * weights, constant V, a single dominant key), scipy's softmax on gathered
+ * dense K/V, and the structural invariants (paged == dense, invariance under
+ * permuting physical blocks, shared prefix == duplicated prefix, GQA == MHA
+ * with replicated heads, prefill row == decode at that length).
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    int32_t num_blocks, block_size, num_kv_heads, num_q_heads, head_dim;
+} oracle_geom;
+
+static double bf16_to_double(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+typedef struct {
+    oracle_geom g;
+    const uint16_t *pool, *q;
+    const int32_t *block_tables, *seq_lens, *cu_q_lens;
+    int32_t max_blocks, B;
+    double scale;
+} attn_problem;
+
+/* One output row: request r, new-token index i, q head h.  `w` (length >= n) receives
+ * the softmax weights; `out` (length d) the result.  Returns n, the number of visible keys. */
+static int64_t attend_row(const attn_problem *p, int r, int i, int h, double *w, double *out) {
+    const oracle_geom *g = &p->g;
+    const int d = g->head_dim, bs = g->block_size, Hkv = g->num_kv_heads, Hq = g->num_q_heads;
+    const int group = Hq / Hkv;
+    const int kvh = h / group;
+    const int64_t L = p->seq_lens[r];
+    const int64_t q_len = p->cu_q_lens ? (p->cu_q_lens[r + 1] - p->cu_q_lens[r]) : 1;
+    const int64_t q_row = p->cu_q_lens ? (p->cu_q_lens[r] + i) : r;
+    const int64_t ctx = L - q_len;
+    const int64_t n = ctx + i + 1;
+    for (int c = 0; c < d; ++c) out[c] = 0.0;
+    if (n <= 0) return 0;
+    const uint16_t *qv = p->q + (q_row * Hq + h) * (int64_t)d;
+    const int32_t *table = p->block_tables + (int64_t)r * p->max_blocks;
+    double smax = -INFINITY;
+    for (int64_t j = 0; j < n; ++j) {
+        const int64_t blk = table[j / bs];
+        const int t = (int)(j % bs);
+        const uint16_t *k = p->pool + ((((blk * 2 + 0) * Hkv + kvh) * bs + t) * (int64_t)d);
+        double s = 0.0;
+        for (int c = 0; c < d; ++c) s += bf16_to_double(qv[c]) * bf16_to_double(k[c]);
+        s *= p->scale;
+        w[j] = s;
+        if (s > smax) smax = s;
+    }
+    double denom = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        w[j] = exp(w[j] - smax);
+        denom += w[j];
+    }
+    for (int64_t j = 0; j < n; ++j) w[j] /= denom;
+    for (int64_t j = 0; j < n; ++j) {
+        const int64_t blk = table[j / bs];
+        const int t = (int)(j % bs);
+        const uint16_t *v = p->pool + ((((blk * 2 + 1) * Hkv + kvh) * bs + t) * (int64_t)d);
+        for (int c = 0; c < d; ++c) out[c] += w[j] * bf16_to_double(v[c]);
+    }
+    return n;
+}
+
+typedef struct {
+    const attn_problem *p;
+    const int32_t *sel_req, *sel_i, *sel_h; /* explicit row list, or NULL */
+    int64_t n_rows;
+    double *out;
+    int tid, nthreads;
+    int64_t max_len;
+    int status;
+} worker_arg;
+
+/* full enumeration: row id -> (r, i, h) in output order [q_row][h] */
+static void row_of(const attn_problem *p, int64_t id, int *r, int *i, int *h) {
+    const int Hq = p->g.num_q_heads;
+    const int64_t q_row = id / Hq;
+    *h = (int)(id % Hq);
+    if (!p->cu_q_lens) {
+        *r = (int)q_row;
+        *i = 0;
+        return;
+    }
+    int lo = 0, hi = p->B; /* last r with cu[r] <= q_row */
+    while (hi - lo > 1) {
+        int mid = (lo + hi) / 2;
+        if (p->cu_q_lens[mid] <= q_row) lo = mid; else hi = mid;
+    }
+    /* skip empty requests that share the same offset */
+    while (lo + 1 < p->B && p->cu_q_lens[lo + 1] <= q_row) ++lo;
+    *r = lo;
+    *i = (int)(q_row - p->cu_q_lens[lo]);
+}
+
+static void *worker(void *argp) {
+    worker_arg *a = (worker_arg *)argp;
+    double *w = (double *)malloc(sizeof(double) * (size_t)(a->max_len > 0 ? a->max_len : 1));
+    if (!w) { a->status = -1; return NULL; }
+    const int d = a->p->g.head_dim;
+    for (int64_t id = a->tid; id < a->n_rows; id += a->nthreads) {
+        int r, i, h;
+        if (a->sel_req) { r = a->sel_req[id]; i = a->sel_i ? a->sel_i[id] : 0; h = a->sel_h[id]; }
+        else row_of(a->p, id, &r, &i, &h);
+        attend_row(a->p, r, i, h, w, a->out + id * d);
+    }
+    free(w);
+    a->status = 0;
+    return NULL;
+}
+
+static int run_rows(const attn_problem *p, const int32_t *sel_req, const int32_t *sel_i, const int32_t *sel_h,
+                    int64_t n_rows, double *out, int nthreads) {
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > 256) nthreads = 256;
+    int64_t max_len = 0;
+    for (int r = 0; r < p->B; ++r) if (p->seq_lens[r] > max_len) max_len = p->seq_lens[r];
+    pthread_t th[256];
+    worker_arg args[256];
+    for (int t = 0; t < nthreads; ++t) {
+        worker_arg a = {p, sel_req, sel_i, sel_h, n_rows, out, t, nthreads, max_len, 0};
+        args[t] = a;
+    }
+    if (nthreads == 1) { worker(&args[0]); return args[0].status; }
+    for (int t = 0; t < nthreads; ++t) pthread_create(&th[t], NULL, worker, &args[t]);
+    int st = 0;
+    for (int t = 0; t < nthreads; ++t) { pthread_join(th[t], NULL); if (args[t].status) st = args[t].status; }
+    return st;
+}
+
+static int check_geom(const oracle_geom *g) {
+    if (g->num_blocks <= 0 || g->block_size <= 0 || g->num_kv_heads <= 0 || g->num_q_heads <= 0 || g->head_dim <= 0) return -1;
+    if (g->num_q_heads % g->num_kv_heads) return -1;
+    return 0;
+}
+
+/* All rows.  cu_q_lens == NULL: decode, out is [B][Hq][d].  Otherwise out is [sum_q][Hq][d]. */
+int glm_oracle_attention(oracle_geom g, const uint16_t *pool, const uint16_t *q, double *out,
+                         const int32_t *block_tables, int32_t max_blocks, const int32_t *seq_lens,
+                         const int32_t *cu_q_lens, int32_t B, float scale, int32_t nthreads) {
+    if (check_geom(&g)) return -1;
+    attn_problem p = {g, pool, q, block_tables, seq_lens, cu_q_lens, max_blocks, B, (double)scale};
+    const int64_t q_rows = cu_q_lens ? cu_q_lens[B] : B;
+    return run_rows(&p, NULL, NULL, NULL, q_rows * g.num_q_heads, out, nthreads);
+}
+
+/* Selected rows only: row k is (request sel_req[k], new-token index sel_i[k] (NULL = 0), q head sel_h[k]);
+ * out is [n_sel][d]. */
+int glm_oracle_attention_rows(oracle_geom g, const uint16_t *pool, const uint16_t *q, double *out,
+                              const int32_t *block_tables, int32_t max_blocks, const int32_t *seq_lens,
+                              const int32_t *cu_q_lens, int32_t B, float scale, const int32_t *sel_req,
+                              const int32_t *sel_i, const int32_t *sel_h, int32_t n_sel, int32_t nthreads) {
+    if (check_geom(&g)) return -1;
+    attn_problem p = {g, pool, q, block_tables, seq_lens, cu_q_lens, max_blocks, B, (double)scale};
+    return run_rows(&p, sel_req, sel_i, sel_h, n_sel, out, nthreads);
+}
+
+/* Softmax weights of one row (length returned; `weights` must hold seq_len entries) and its output. */
+int64_t glm_oracle_attention_weights(oracle_geom g, const uint16_t *pool, const uint16_t *q,
+                                     const int32_t *block_tables, int32_t max_blocks, const int32_t *seq_lens,
+                                     const int32_t *cu_q_lens, int32_t B, float scale, int32_t r, int32_t i,
+                                     int32_t h, double *weights, double *out) {
+    if (check_geom(&g)) return -1;
+    attn_problem p = {g, pool, q, block_tables, seq_lens, cu_q_lens, max_blocks, B, (double)scale};
+    return attend_row(&p, r, i, h, weights, out);
+}
+
+/* Fork / copy-on-write: for each pair, the first n_tokens[k] token rows of every (plane, kv head)
+ * of block src[k] are copied to block dst[k]; every other byte of the pool is left as it was. */
+int glm_oracle_fork_copy(oracle_geom g, uint16_t *pool, const int32_t *src_ids, const int32_t *dst_ids,
+                         const int32_t *n_tokens, int32_t n_pairs) {
+    if (check_geom(&g)) return -1;
+    const int64_t d = g.head_dim, bs = g.block_size, Hkv = g.num_kv_heads;
+    for (int k = 0; k < n_pairs; ++k) {
+        const int64_t s = src_ids[k], t = dst_ids[k];
+        const int nt = n_tokens[k];
+        if (s < 0 || s >= g.num_blocks || t < 0 || t >= g.num_blocks || nt < 0 || nt > bs) return -2;
+        for (int p = 0; p < 2; ++p)
+            for (int h = 0; h < Hkv; ++h)
+                for (int tok = 0; tok < nt; ++tok)
+                    for (int c = 0; c < d; ++c) {
+                        const int64_t off = (((p * Hkv + h) * bs + tok) * d + c);
+                        pool[t * 2 * Hkv * bs * d + off] = pool[s * 2 * Hkv * bs * d + off];
+                    }
+    }
+    return 0;
+}
+
+/* Gather of whole blocks between two buffers of the same block geometry:
+ * dst[dst_ids[k]] = src[src_ids[k]]; a NULL list means the identity 0..n-1. */
+int glm_oracle_gather(oracle_geom g, const uint16_t *src_base, const int32_t *src_ids, uint16_t *dst_base,
+                      const int32_t *dst_ids, int32_t n) {
+    if (check_geom(&g)) return -1;
+    const int64_t blk = 2LL * g.num_kv_heads * g.block_size * g.head_dim;
+    for (int k = 0; k < n; ++k) {
+        const int64_t s = src_ids ? src_ids[k] : k, t = dst_ids ? dst_ids[k] : k;
+        if (s < 0 || t < 0) return -2;
+        for (int64_t e = 0; e < blk; ++e) dst_base[t * blk + e] = src_base[s * blk + e];
+    }
+    return 0;
+}

@@ -1,0 +1,252 @@
+"""Pins of the CPU oracle against things it does not compute itself: a pure-Python brute
+force, scipy's softmax on dense K/V, closed forms and the structural invariants of
+output-preserving prefix reuse (paper Sec. 2.4: reused prefix blocks leave outputs unchanged)."""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+import workloads as W
+from util import bf16_to_f64, brute_force_row, dense_kv, f32_to_bf16, q_row_index, visible
+
+
+def _oracle_all(w, **kw):
+    return oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, cu_q_lens=w.cu_q_lens, **kw)
+
+
+def _small_decode(seed, suffix, prefix=32, heads=(4, 2), d=16, bs=4, **kw):
+    B = len(suffix)
+    return W.custom_decode(seed, prefix_groups=[list(range(B))] if prefix else [], prefix_tokens=[prefix] if prefix else [],
+                           suffix_tokens=suffix, num_q_heads=heads[0], num_kv_heads=heads[1], head_dim=d,
+                           block_size=bs, **kw)
+
+
+# ---- brute force on 1-4 token cases (and a bit beyond), decode and prefill, GQA and MHA
+
+@pytest.mark.parametrize("L", [1, 2, 3, 4, 7])
+@pytest.mark.parametrize("heads", [(2, 2), (4, 2), (6, 1)])
+def test_brute_force_tiny_decode(L, heads):
+    w = W.custom_decode(100 + L, prefix_groups=[], prefix_tokens=[], suffix_tokens=[L - 1, L - 1, max(0, L - 2)],
+                        num_q_heads=heads[0], num_kv_heads=heads[1], head_dim=8, block_size=2)
+    out = _oracle_all(w)
+    for r in range(w.B):
+        for h in range(heads[0]):
+            wts, ref = brute_force_row(w, r, 0, h)
+            np.testing.assert_allclose(out[r, h], ref, rtol=0, atol=1e-14)
+            ow, oo = oracle.attention_weights(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, r, h)
+            np.testing.assert_allclose(ow, wts, rtol=0, atol=1e-15)
+            np.testing.assert_array_equal(oo, out[r, h])
+
+
+def test_single_token_is_exactly_v0():
+    w = W.custom_decode(7, prefix_groups=[], prefix_tokens=[], suffix_tokens=[0, 0, 0], num_q_heads=4,
+                        num_kv_heads=2, head_dim=16, block_size=4)
+    out = _oracle_all(w)
+    for r in range(3):
+        blk = int(w.block_tables[r, 0])
+        for h in range(4):
+            np.testing.assert_array_equal(out[r, h], bf16_to_f64(w.pool[blk, 1, h // 2, 0]))
+
+
+def test_brute_force_tiny_prefill():
+    w = W.custom_prefill(11, prefix_groups=[[0, 1]], prefix_tokens=[4], q_lens=[3, 1, 4], num_q_heads=4,
+                         num_kv_heads=2, head_dim=8, block_size=2)
+    out = _oracle_all(w)
+    for r in range(w.B):
+        for i in range(int(w.q_lens[r])):
+            for h in range(4):
+                _, ref = brute_force_row(w, r, i, h)
+                np.testing.assert_allclose(out[q_row_index(w, r, i), h], ref, rtol=0, atol=1e-14)
+
+
+# ---- reduces to a library routine: softmax(scale * K q) @ V on K/V gathered through the table
+
+@pytest.mark.parametrize("cfg", ["decode", "prefill"])
+def test_matches_scipy_softmax_on_dense_kv(cfg):
+    if cfg == "decode":
+        w = _small_decode(21, [0, 5, 17, 33, 2], prefix=48, heads=(8, 2), d=32, bs=16)
+    else:
+        w = W.custom_prefill(22, prefix_groups=[[0, 1, 2]], prefix_tokens=[40], q_lens=[9, 1, 17, 5], num_q_heads=8,
+                             num_kv_heads=2, head_dim=32, block_size=16)
+    out = _oracle_all(w)
+    G = w.geom.group
+    for r in range(w.B):
+        ql = 1 if w.q_lens is None else int(w.q_lens[r])
+        for i in range(ql):
+            n = visible(w, r, i)
+            for h in range(w.geom.num_q_heads):
+                K, V = dense_kv(w, r, h // G, n)
+                qv = bf16_to_f64(w.q[q_row_index(w, r, i), h])
+                ref = scipy.special.softmax(float(np.float32(w.scale)) * (K @ qv)) @ V
+                np.testing.assert_allclose(out[q_row_index(w, r, i), h], ref, rtol=0, atol=1e-13)
+
+
+# ---- invariants
+
+def test_invariant_under_physical_block_permutation():
+    a = _small_decode(31, [3, 9, 20, 0], permute=False)
+    b = _small_decode(31, [3, 9, 20, 0], permute=True)
+    # same seed draws the same permutation stream but different ids: remap b's data onto a's content instead
+    perm = np.random.Generator(np.random.PCG64(5)).permutation(a.geom.num_blocks)
+    pool2 = np.empty_like(a.pool); pool2[perm] = a.pool
+    tables2 = np.where(a.block_tables >= 0, perm[np.clip(a.block_tables, 0, None)], -1).astype(np.int32)
+    o1 = _oracle_all(a)
+    o2 = oracle.attention(a.geom, pool2, a.q, tables2, a.seq_lens, a.scale)
+    np.testing.assert_array_equal(o1, o2)
+    assert b.block_tables.shape == a.block_tables.shape
+
+
+def test_shared_prefix_equals_duplicated_prefix():
+    w = _small_decode(41, [1, 6, 11, 4, 0, 9], prefix=24, occupancy=0.3)
+    o_shared = _oracle_all(w)
+    bs = w.geom.block_size
+    npre = 24 // bs
+    used = set(int(x) for x in w.live_block_ids())
+    free = [b for b in range(w.geom.num_blocks) if b not in used]
+    pool = w.pool.copy(); tables = w.block_tables.copy()
+    for r in range(1, w.B):
+        for i in range(npre):
+            nb = free.pop()
+            pool[nb] = w.pool[tables[r, i]]
+            tables[r, i] = nb
+    assert len(set(int(x) for x in tables[:, :npre].ravel())) == npre * w.B
+    o_dup = oracle.attention(w.geom, pool, w.q, tables, w.seq_lens, w.scale)
+    np.testing.assert_array_equal(o_shared, o_dup)
+
+
+def test_weights_sum_to_one_and_constant_v():
+    w = _small_decode(51, [0, 7, 30], prefix=16, heads=(4, 2), d=16, bs=4)
+    for r in range(w.B):
+        for h in range(4):
+            wt, _ = oracle.attention_weights(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, r, h)
+            assert len(wt) == int(w.seq_lens[r])
+            assert abs(math.fsum(wt) - 1.0) < 1e-15 * 8
+            assert (wt > 0).all()
+    c = f32_to_bf16(np.float32(1.3125))
+    w.pool[:, 1] = c
+    out = _oracle_all(w)
+    np.testing.assert_allclose(out, 1.3125, rtol=0, atol=1e-15)
+
+
+def test_zero_query_and_equal_keys_give_mean_of_v():
+    w = _small_decode(61, [2, 13], prefix=8, heads=(2, 1), d=8, bs=4)
+    w.q[:] = 0
+    out = _oracle_all(w)
+    for r in range(w.B):
+        n = int(w.seq_lens[r])
+        _, V = dense_kv(w, r, 0, n)
+        np.testing.assert_allclose(out[r, 0], V.mean(0), rtol=0, atol=1e-14)
+    w2 = _small_decode(62, [2, 13], prefix=8, heads=(2, 1), d=8, bs=4)
+    w2.pool[:, 0] = w2.pool[0, 0, 0, 0]   # every key row identical
+    out2 = _oracle_all(w2)
+    for r in range(w2.B):
+        _, V = dense_kv(w2, r, 0, int(w2.seq_lens[r]))
+        np.testing.assert_allclose(out2[r, 1], V.mean(0), rtol=0, atol=1e-14)
+
+
+def test_two_keys_closed_form():
+    # d=2, q=(1,0), k0=(0,0), k1=(4,0), scale=0.25 -> scores (0,1), weights 1/(1+e), e/(1+e)
+    geom = W.Geometry(2, 2, 1, 1, 2)
+    pool = np.zeros((2, 2, 1, 2, 2), np.uint16)
+    pool[1, 0, 0, 1] = f32_to_bf16(np.array([4.0, 0.0], np.float32))
+    pool[1, 1, 0, 0] = f32_to_bf16(np.array([2.0, -1.0], np.float32))
+    pool[1, 1, 0, 1] = f32_to_bf16(np.array([-3.0, 0.5], np.float32))
+    q = f32_to_bf16(np.array([[[1.0, 0.0]]], np.float32))
+    out = oracle.attention(geom, pool, q, np.array([[1]], np.int32), np.array([2], np.int32), 0.25)
+    w0, w1 = 1 / (1 + math.e), math.e / (1 + math.e)
+    np.testing.assert_allclose(out[0, 0], [w0 * 2.0 + w1 * -3.0, w0 * -1.0 + w1 * 0.5], rtol=0, atol=1e-15)
+
+
+def test_dominant_key_no_overflow():
+    w = _small_decode(71, [10], prefix=0, heads=(1, 1), d=4, bs=4)
+    # scores: key 5 gets +600*scale... make q=(16,0,0,0), keys zero except key 5 = (64,0,0,0), scale 0.5 -> s=512
+    w.q[:] = 0; w.q[0, 0, 0] = f32_to_bf16(np.float32(16.0))
+    w.pool[:, 0] = 0
+    blk = int(w.block_tables[0, 1])
+    w.pool[blk, 0, 0, 1, 0] = f32_to_bf16(np.float32(64.0))
+    out = oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, 0.5)
+    assert np.isfinite(out).all()
+    np.testing.assert_allclose(out[0, 0], bf16_to_f64(w.pool[blk, 1, 0, 1]), rtol=0, atol=1e-200)
+
+
+def test_prefill_row_equals_decode_at_that_length():
+    w = W.custom_prefill(81, prefix_groups=[[0, 1]], prefix_tokens=[20], q_lens=[6, 3], num_q_heads=4, num_kv_heads=2,
+                         head_dim=16, block_size=4)
+    out = _oracle_all(w)
+    for r in range(w.B):
+        ctx = int(w.seq_lens[r]) - int(w.q_lens[r])
+        for i in range(int(w.q_lens[r])):
+            qd = np.zeros((w.B,) + w.q.shape[1:], np.uint16)
+            qd[r] = w.q[q_row_index(w, r, i)]
+            sl = w.seq_lens.copy(); sl[r] = ctx + i + 1
+            od = oracle.attention(w.geom, w.pool, qd, w.block_tables, sl, w.scale)
+            np.testing.assert_array_equal(od[r], out[q_row_index(w, r, i)])
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    w = _small_decode(91, [4, 12, 1], prefix=12, heads=(6, 2), d=8, bs=4)
+    out = _oracle_all(w)
+    G = 3
+    pool_mha = np.repeat(w.pool, G, axis=2)   # kv head k -> q heads 3k..3k+2
+    geom = W.Geometry(w.geom.num_blocks, 4, 6, 6, 8)
+    out_mha = oracle.attention(geom, pool_mha, w.q, w.block_tables, w.seq_lens, w.scale)
+    np.testing.assert_array_equal(out, out_mha)
+
+
+def test_empty_rows_are_zero():
+    w = _small_decode(95, [3, 0], prefix=0, heads=(2, 1), d=8, bs=4)
+    w.seq_lens[1] = 0
+    out = _oracle_all(w)
+    assert (out[1] == 0).all() and np.abs(out[0]).sum() > 0
+    wp = W.custom_prefill(96, prefix_groups=[], prefix_tokens=[], q_lens=[2, 0, 3], num_q_heads=2, num_kv_heads=1,
+                          head_dim=8, block_size=4)
+    outp = _oracle_all(wp)
+    assert outp.shape[0] == 5
+    _, ref = brute_force_row(wp, 2, 0, 1)
+    np.testing.assert_allclose(outp[2, 1], ref, atol=1e-14)
+
+
+def test_thread_count_does_not_change_results():
+    w = _small_decode(97, [5, 9, 2, 31], prefix=16)
+    np.testing.assert_array_equal(_oracle_all(w, nthreads=1), _oracle_all(w, nthreads=5))
+    sel_r = np.array([3, 0, 2], np.int32); sel_h = np.array([1, 3, 0], np.int32)
+    rows = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, sel_r, sel_h)
+    full = _oracle_all(w)
+    for k in range(3):
+        np.testing.assert_array_equal(rows[k], full[sel_r[k], sel_h[k]])
+
+
+# ---- copy operations, against numpy slicing written here
+
+def test_fork_copy_matches_slicing_and_leaves_the_rest():
+    rng = np.random.default_rng(3)
+    geom = W.Geometry(12, 4, 3, 3, 8)
+    pool = rng.integers(0, 65536, size=(12, 2, 3, 4, 8), dtype=np.uint16)
+    src = np.array([0, 0, 5, 7], np.int32); dst = np.array([1, 2, 9, 11], np.int32); nt = np.array([1, 4, 0, 3], np.int32)
+    ref = pool.copy()
+    for s, t, n in zip(src, dst, nt):
+        ref[t, :, :, :n, :] = pool[s, :, :, :n, :]
+    got = pool.copy()
+    oracle.fork_copy(geom, got, src, dst, nt)
+    np.testing.assert_array_equal(got, ref)
+    assert (got[9] == pool[9]).all() and (got[1, :, :, 1:] == pool[1, :, :, 1:]).all()
+
+
+def test_gather_matches_indexing_and_inverts():
+    rng = np.random.default_rng(4)
+    geom = W.Geometry(10, 4, 2, 2, 8)
+    src = rng.integers(0, 65536, size=(10, 2, 2, 4, 8), dtype=np.uint16)
+    ids = np.array([7, 2, 9, 0], np.int32)
+    staged = np.zeros((4, 2, 2, 4, 8), np.uint16)
+    oracle.gather(geom, src, ids, staged, None)
+    np.testing.assert_array_equal(staged, src[ids])
+    back = np.full_like(src, 0xABCD)
+    oracle.gather(geom, staged, None, back, ids)
+    np.testing.assert_array_equal(back[ids], src[ids])
+    untouched = np.setdiff1d(np.arange(10), ids)
+    assert (back[untouched] == 0xABCD).all()
+    both = np.zeros_like(src)
+    oracle.gather(geom, src, np.array([1, 3], np.int32), both, np.array([8, 4], np.int32))
+    np.testing.assert_array_equal(both[[8, 4]], src[[1, 3]])

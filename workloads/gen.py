@@ -1,0 +1,440 @@
+"""Generators for the five benchmark configurations and for small custom cases.
+
+Conventions
+-----------
+* KV pool element (blk, p, hkv, t, c) lives at ((((blk*2+p)*Hkv+hkv)*bs+t)*d+c,
+  p = 0 for K and 1 for V, stored as bf16 bit patterns in a numpy uint16 array
+  of shape [num_blocks, 2, Hkv, bs, d].
+* Q is uint16 (bf16 bits) of shape [sum_q, Hq, d]; decode has one row per branch.
+* block_tables is int32 [B, max_blocks]; entries past ceil(seq_len/bs) are -1.
+* seq_lens counts every token whose K/V is in the cache, including the token(s)
+  being attended from (decode: the new token; prefill: the whole new suffix).
+* Only live blocks hold random data; every other block holds a large finite
+  sentinel so that a stray read shows up as a parity failure rather than a NaN.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+BASE_SEED = 20251101
+SENTINEL_BITS = 0x4600  # bf16 8192.0
+CONFIG_NAMES = ("tiny_decode", "llama8b_decode", "prefill_on_prefix", "tree_decode_70b", "eviction_churn")
+
+
+@dataclass(frozen=True)
+class Geometry:
+    num_blocks: int
+    block_size: int
+    num_kv_heads: int
+    num_q_heads: int
+    head_dim: int
+
+    @property
+    def block_elems(self) -> int:
+        return 2 * self.num_kv_heads * self.block_size * self.head_dim
+
+    @property
+    def block_bytes(self) -> int:
+        return 2 * self.block_elems
+
+    @property
+    def group(self) -> int:
+        return self.num_q_heads // self.num_kv_heads
+
+
+@dataclass
+class Workload:
+    name: str
+    geom: Geometry
+    pool: np.ndarray            # uint16 [num_blocks, 2, Hkv, bs, d]
+    q: np.ndarray               # uint16 [sum_q, Hq, d]
+    block_tables: np.ndarray    # int32 [B, max_blocks]
+    seq_lens: np.ndarray        # int32 [B]
+    scale: float                # fp32 value
+    q_lens: Optional[np.ndarray] = None     # int32 [B]; None = decode (1 each)
+    cu_q_lens: Optional[np.ndarray] = None  # int32 [B+1]
+    meta: Dict = field(default_factory=dict)
+
+    @property
+    def B(self) -> int:
+        return int(self.seq_lens.shape[0])
+
+    @property
+    def max_blocks(self) -> int:
+        return int(self.block_tables.shape[1])
+
+    @property
+    def sum_q(self) -> int:
+        return int(self.q.shape[0])
+
+    @property
+    def is_decode(self) -> bool:
+        return self.q_lens is None
+
+    def live_block_ids(self) -> np.ndarray:
+        """Distinct physical blocks referenced by the batch (each counted once)."""
+        bs = self.geom.block_size
+        ids = []
+        for r in range(self.B):
+            nb = -(-int(self.seq_lens[r]) // bs)
+            ids.append(self.block_tables[r, :nb])
+        if not ids:
+            return np.zeros(0, np.int64)
+        return np.unique(np.concatenate(ids).astype(np.int64))
+
+    def unique_kv_bytes(self) -> int:
+        """K/V bytes of distinct cached tokens: a block referenced by several
+        branches counts once, and a partly filled block counts its filled rows."""
+        g = self.geom
+        bs = g.block_size
+        fill: Dict[int, int] = {}
+        for r in range(self.B):
+            L = int(self.seq_lens[r])
+            nb = -(-L // bs)
+            for i in range(nb):
+                n = min(bs, L - i * bs)
+                b = int(self.block_tables[r, i])
+                if fill.get(b, 0) < n:
+                    fill[b] = n
+        tokens = sum(fill.values())
+        return tokens * 2 * g.num_kv_heads * g.head_dim * 2
+
+    def logical_kv_bytes(self) -> int:
+        g = self.geom
+        return int(self.seq_lens.astype(np.int64).sum()) * 2 * g.num_kv_heads * g.head_dim * 2
+
+    def visible_pairs(self) -> int:
+        """Number of (query row, visible key) pairs per q head."""
+        if self.q_lens is None:
+            return int(self.seq_lens.astype(np.int64).sum())
+        tot = 0
+        for r in range(self.B):
+            L = int(self.seq_lens[r]); ql = int(self.q_lens[r]); ctx = L - ql
+            tot += ql * ctx + ql * (ql + 1) // 2
+        return tot
+
+    def flops(self) -> int:
+        return self.visible_pairs() * self.geom.num_q_heads * 4 * self.geom.head_dim
+
+
+@dataclass
+class ChurnStep:
+    """Index lists of one eviction-churn step (all int32)."""
+    fork_src: np.ndarray
+    fork_dst: np.ndarray
+    fork_ntok: np.ndarray
+    evict_ids: np.ndarray       # blocks packed out of the pool into staging slots 0..n-1
+    readmit_ids: np.ndarray     # free slots the staged blocks return to
+    block_tables: np.ndarray    # tables after the fork and the re-admission
+
+
+# --------------------------------------------------------------------------- bf16 helpers
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bf16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def config_seed(index: int) -> int:
+    return BASE_SEED + int(index)
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def _normal_bf16(rng: np.random.Generator, shape) -> np.ndarray:
+    return f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+
+
+def _new_pool(geom: Geometry) -> np.ndarray:
+    return np.full((geom.num_blocks, 2, geom.num_kv_heads, geom.block_size, geom.head_dim), SENTINEL_BITS, np.uint16)
+
+
+def _fill_blocks(pool: np.ndarray, ids: np.ndarray, rng: np.random.Generator, slab: int = 2048) -> None:
+    ids = np.asarray(ids, np.int64)
+    for s in range(0, ids.size, slab):
+        part = ids[s:s + slab]
+        pool[part] = _normal_bf16(rng, (part.size,) + pool.shape[1:])
+
+
+def _pool_size(live: int, occupancy: float) -> int:
+    return max(live + 1, int(math.ceil(live / occupancy)))
+
+
+class _Alloc:
+    """Hands out physical block ids in a seeded random order."""
+
+    def __init__(self, num_blocks: int, rng: np.random.Generator, permute: bool = True):
+        self.order = rng.permutation(num_blocks) if permute else np.arange(num_blocks)
+        self.pos = 0
+
+    def take(self, n: int) -> np.ndarray:
+        if self.pos + n > self.order.size:
+            raise ValueError("pool too small")
+        out = self.order[self.pos:self.pos + n]
+        self.pos += n
+        return out.astype(np.int32)
+
+    def free_ids(self) -> np.ndarray:
+        return self.order[self.pos:].astype(np.int32)
+
+
+def _tables(rows: Sequence[np.ndarray], max_blocks: Optional[int] = None) -> np.ndarray:
+    mb = max(1, max((len(r) for r in rows), default=1))
+    if max_blocks is not None:
+        mb = max(mb, max_blocks)
+    t = np.full((len(rows), mb), -1, np.int32)
+    for i, r in enumerate(rows):
+        t[i, :len(r)] = r
+    return t
+
+
+def _cu(q_lens: np.ndarray) -> np.ndarray:
+    cu = np.zeros(q_lens.size + 1, np.int32)
+    np.cumsum(q_lens, out=cu[1:])
+    return cu
+
+
+def _scale(d: int) -> float:
+    return float(np.float32(1.0 / math.sqrt(d)))
+
+
+# --------------------------------------------------------------------------- generic builders
+
+def custom_decode(seed: int, *, prefix_groups: Sequence[Sequence[int]], prefix_tokens: Sequence[int],
+                  suffix_tokens: Sequence[int], num_q_heads: int, num_kv_heads: int, head_dim: int,
+                  block_size: int = 16, occupancy: float = 0.9, permute: bool = True,
+                  extra_table_cols: int = 0, name: str = "custom_decode") -> Workload:
+    """Decode batch: group k's branches share prefix_tokens[k] tokens (full blocks
+    shared, any partly filled prefix tail is private to each branch), then each
+    branch r has suffix_tokens[r] private tokens plus the one new token."""
+    rng = _rng(seed)
+    bs = block_size
+    B = len(suffix_tokens)
+    group_of = np.full(B, -1, np.int64)
+    for k, members in enumerate(prefix_groups):
+        for r in members:
+            group_of[r] = k
+    shared_nb = [int(p) // bs for p in prefix_tokens]
+    seq = np.zeros(B, np.int32)
+    for r in range(B):
+        p = int(prefix_tokens[group_of[r]]) if group_of[r] >= 0 else 0
+        seq[r] = p + int(suffix_tokens[r]) + 1
+    live = sum(shared_nb)
+    for r in range(B):
+        sn = shared_nb[group_of[r]] if group_of[r] >= 0 else 0
+        live += -(-int(seq[r]) // bs) - sn
+    geom = Geometry(_pool_size(live, occupancy), bs, num_kv_heads, num_q_heads, head_dim)
+    alloc = _Alloc(geom.num_blocks, rng, permute)
+    shared = [alloc.take(n) for n in shared_nb]
+    rows = []
+    for r in range(B):
+        sh = shared[group_of[r]] if group_of[r] >= 0 else np.zeros(0, np.int32)
+        nb = -(-int(seq[r]) // bs)
+        rows.append(np.concatenate([sh, alloc.take(nb - sh.size)]))
+    tables = _tables(rows, max((len(x) for x in rows), default=1) + extra_table_cols)
+    pool = _new_pool(geom)
+    used = np.unique(np.concatenate(rows)) if rows else np.zeros(0, np.int64)
+    _fill_blocks(pool, used, rng)
+    q = _normal_bf16(rng, (B, num_q_heads, head_dim))
+    return Workload(name, geom, pool, q, tables, seq, _scale(head_dim),
+                    meta={"prefix_groups": [list(m) for m in prefix_groups], "prefix_tokens": list(prefix_tokens)})
+
+
+def custom_prefill(seed: int, *, prefix_groups: Sequence[Sequence[int]], prefix_tokens: Sequence[int],
+                   q_lens: Sequence[int], num_q_heads: int, num_kv_heads: int, head_dim: int,
+                   block_size: int = 16, occupancy: float = 0.9, permute: bool = True,
+                   name: str = "custom_prefill") -> Workload:
+    """Prefill batch: branch r appends q_lens[r] new tokens (already written to the
+    pool) after its group's cached prefix; seq_len = prefix + q_len."""
+    rng = _rng(seed)
+    bs = block_size
+    B = len(q_lens)
+    group_of = np.full(B, -1, np.int64)
+    for k, members in enumerate(prefix_groups):
+        for r in members:
+            group_of[r] = k
+    shared_nb = [int(p) // bs for p in prefix_tokens]
+    ql = np.asarray(q_lens, np.int32)
+    seq = np.zeros(B, np.int32)
+    for r in range(B):
+        p = int(prefix_tokens[group_of[r]]) if group_of[r] >= 0 else 0
+        seq[r] = p + int(ql[r])
+    live = sum(shared_nb)
+    for r in range(B):
+        sn = shared_nb[group_of[r]] if group_of[r] >= 0 else 0
+        live += -(-int(seq[r]) // bs) - sn
+    geom = Geometry(_pool_size(live, occupancy), bs, num_kv_heads, num_q_heads, head_dim)
+    alloc = _Alloc(geom.num_blocks, rng, permute)
+    shared = [alloc.take(n) for n in shared_nb]
+    rows = []
+    for r in range(B):
+        sh = shared[group_of[r]] if group_of[r] >= 0 else np.zeros(0, np.int32)
+        nb = -(-int(seq[r]) // bs)
+        rows.append(np.concatenate([sh, alloc.take(nb - sh.size)]))
+    tables = _tables(rows)
+    pool = _new_pool(geom)
+    used = np.unique(np.concatenate(rows)) if rows else np.zeros(0, np.int64)
+    _fill_blocks(pool, used, rng)
+    q = _normal_bf16(rng, (int(ql.sum()), num_q_heads, head_dim))
+    return Workload(name, geom, pool, q, tables, seq, _scale(head_dim), q_lens=ql, cu_q_lens=_cu(ql),
+                    meta={"prefix_groups": [list(m) for m in prefix_groups], "prefix_tokens": list(prefix_tokens)})
+
+
+# --------------------------------------------------------------------------- the five configurations
+
+def tiny_decode(seed: Optional[int] = None) -> Workload:
+    """8 branches on one 128-token prefix, suffix U{0..64}, 4/4 heads, d=64."""
+    seed = config_seed(0) if seed is None else seed
+    sfx = _rng(seed ^ 0x5EED).integers(0, 65, size=8)
+    w = custom_decode(seed, prefix_groups=[list(range(8))], prefix_tokens=[128], suffix_tokens=sfx,
+                      num_q_heads=4, num_kv_heads=4, head_dim=64, occupancy=0.5, name="tiny_decode")
+    return w
+
+
+def llama8b_decode(seed: Optional[int] = None, *, branches: int = 64, prefixes: int = 4,
+                   prefix_tokens: int = 2048, suffix_lo: int = 128, suffix_hi: int = 1024) -> Workload:
+    """64 branches on 4 shared 2048-token graph-context prefixes, suffix U{128..1024},
+    32 Q / 8 KV heads, d=128.  Branches are dealt to prefixes in a seeded shuffle."""
+    seed = config_seed(1) if seed is None else seed
+    r2 = _rng(seed ^ 0x5EED)
+    sfx = r2.integers(suffix_lo, suffix_hi + 1, size=branches)
+    order = r2.permutation(branches)
+    per = branches // prefixes
+    groups = [sorted(int(x) for x in order[k * per:(k + 1) * per]) for k in range(prefixes)]
+    return custom_decode(seed, prefix_groups=groups, prefix_tokens=[prefix_tokens] * prefixes, suffix_tokens=sfx,
+                         num_q_heads=32, num_kv_heads=8, head_dim=128, name="llama8b_decode")
+
+
+def prefill_on_prefix(seed: Optional[int] = None, *, branches: int = 16, prefix_tokens: int = 4096,
+                      q_len: int = 512) -> Workload:
+    """16 branches each appending 512 tokens onto one cached 4096-token prefix."""
+    seed = config_seed(2) if seed is None else seed
+    return custom_prefill(seed, prefix_groups=[list(range(branches))], prefix_tokens=[prefix_tokens],
+                          q_lens=[q_len] * branches, num_q_heads=32, num_kv_heads=8, head_dim=128,
+                          name="prefill_on_prefix")
+
+
+def tree_decode_70b(seed: Optional[int] = None, *, root_tokens: int = 8192, mids: int = 8, mid_tokens: int = 1024,
+                    leaves_per_mid: int = 32, suffix_tokens: int = 256, num_q_heads: int = 64,
+                    num_kv_heads: int = 8, head_dim: int = 128, block_size: int = 16) -> Workload:
+    """Three-level prefix tree: root graph context shared by all branches, one
+    sub-query prefix per group of branches, then a private suffix plus the new token."""
+    seed = config_seed(3) if seed is None else seed
+    rng = _rng(seed)
+    bs = block_size
+    B = mids * leaves_per_mid
+    root_nb, mid_nb = root_tokens // bs, mid_tokens // bs
+    L = root_nb * bs + mid_nb * bs + suffix_tokens + 1
+    leaf_nb = -(-L // bs) - root_nb - mid_nb
+    live = root_nb + mids * mid_nb + B * leaf_nb
+    geom = Geometry(_pool_size(live, 0.9), bs, num_kv_heads, num_q_heads, head_dim)
+    alloc = _Alloc(geom.num_blocks, rng)
+    root = alloc.take(root_nb)
+    mid = [alloc.take(mid_nb) for _ in range(mids)]
+    order = rng.permutation(B)
+    rows: List[np.ndarray] = [np.zeros(0, np.int32)] * B
+    groups = []
+    for k in range(mids):
+        members = sorted(int(x) for x in order[k * leaves_per_mid:(k + 1) * leaves_per_mid])
+        groups.append(members)
+        for r in members:
+            rows[r] = np.concatenate([root, mid[k], alloc.take(leaf_nb)])
+    tables = _tables(rows)
+    pool = _new_pool(geom)
+    _fill_blocks(pool, np.unique(np.concatenate(rows)), rng)
+    q = _normal_bf16(rng, (B, num_q_heads, head_dim))
+    seq = np.full(B, L, np.int32)
+    return Workload("tree_decode_70b", geom, pool, q, tables, seq, _scale(head_dim), meta={"mid_groups": groups})
+
+
+def eviction_churn(seed: Optional[int] = None, *, branches: int = 128, family: int = 4, median: int = 2048,
+                   sigma: float = 1.0, lo: int = 256, hi: int = 32768, occupancy: float = 0.8,
+                   num_q_heads: int = 32, num_kv_heads: int = 8, head_dim: int = 128,
+                   block_size: int = 16) -> Workload:
+    """Fixed pool at 80 % occupancy, physical ids permuted, lognormal lengths,
+    branches in fork families of 4 that share the full blocks before a fork point
+    that is not block aligned (each member owns its copy of the partly filled block)."""
+    seed = config_seed(4) if seed is None else seed
+    rng = _rng(seed)
+    bs = block_size
+    B = branches
+    seq = np.clip(np.rint(np.exp(rng.normal(math.log(median), sigma, size=B))), lo, hi).astype(np.int32)
+    nfam = B // family
+    fams = [list(range(k * family, (k + 1) * family)) for k in range(nfam)]
+    fork_pts = []
+    live = 0
+    for members in fams:
+        shortest = int(min(seq[r] for r in members))
+        fp = int(rng.integers(shortest // 4, (3 * shortest) // 4 + 1))
+        if fp % bs == 0:
+            fp += 1 + int(rng.integers(0, bs - 1))
+        fork_pts.append(fp)
+        live += fp // bs + sum(-(-int(seq[r]) // bs) - fp // bs for r in members)
+    geom = Geometry(_pool_size(live, occupancy), bs, num_kv_heads, num_q_heads, head_dim)
+    alloc = _Alloc(geom.num_blocks, rng)
+    rows: List[np.ndarray] = [np.zeros(0, np.int32)] * B
+    for members, fp in zip(fams, fork_pts):
+        sh = alloc.take(fp // bs)
+        for r in members:
+            rows[r] = np.concatenate([sh, alloc.take(-(-int(seq[r]) // bs) - sh.size)])
+    tables = _tables(rows)
+    pool = _new_pool(geom)
+    _fill_blocks(pool, np.unique(np.concatenate(rows)), rng)
+    q = _normal_bf16(rng, (B, num_q_heads, head_dim))
+    return Workload("eviction_churn", geom, pool, q, tables, seq, _scale(head_dim),
+                    meta={"families": fams, "fork_points": fork_pts, "free_ids": alloc.free_ids()})
+
+
+def churn_step(w: Workload, step: int, *, n_fork: int = 32, readmit_frac: float = 0.02,
+               seed: Optional[int] = None) -> ChurnStep:
+    """Index lists of churn step `step` on workload `w` (which is not modified).
+
+    (1) n_fork branches get a private copy of their partly filled last block: src is
+    the block in the table, dst a free slot, n_tokens the rows filled so far.
+    (2) readmit_frac of the live blocks are packed to a staging buffer and return
+    into other free slots.  The returned tables point at the new slots."""
+    rng = _rng((config_seed(4) if seed is None else seed) * 1000003 + step + 1)
+    bs = w.geom.block_size
+    tables = w.block_tables.copy()
+    used = np.zeros(w.geom.num_blocks, bool)
+    used[w.live_block_ids()] = True
+    free = rng.permutation(np.flatnonzero(~used)).astype(np.int32)
+    reqs = rng.choice(w.B, size=min(n_fork, w.B), replace=False)
+    src, dst, ntok = [], [], []
+    fpos = 0
+    for r in reqs:
+        L = int(w.seq_lens[r])
+        if L == 0:
+            continue
+        last = (L - 1) // bs
+        src.append(int(tables[r, last])); dst.append(int(free[fpos])); ntok.append(L - last * bs)
+        tables[r, last] = free[fpos]
+        fpos += 1
+    live_now = np.unique(np.concatenate([tables[r, :-(-int(w.seq_lens[r]) // bs)] for r in range(w.B)]))
+    fork_dst = set(dst)
+    cand = np.array([b for b in live_now if int(b) not in fork_dst], np.int32)
+    n_re = min(int(round(readmit_frac * live_now.size)), free.size - fpos, cand.size)
+    evict = rng.choice(cand, size=n_re, replace=False).astype(np.int32)
+    readmit = free[fpos:fpos + n_re].astype(np.int32)
+    remap = np.arange(w.geom.num_blocks, dtype=np.int32)
+    remap[evict] = readmit
+    valid = tables >= 0
+    tables[valid] = remap[tables[valid]]
+    return ChurnStep(np.asarray(src, np.int32), np.asarray(dst, np.int32), np.asarray(ntok, np.int32),
+                     evict, readmit, tables)
+
+
+def make_config(index: int, seed: Optional[int] = None) -> Workload:
+    return (tiny_decode, llama8b_decode, prefill_on_prefix, tree_decode_70b, eviction_churn)[index](seed)
