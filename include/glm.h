@@ -1,0 +1,185 @@
+/*
+ * glm.h - C ABI of the shared-prefix paged-KV attention library for MI355X (gfx950).
+ *
+ * The library is the GPU data path underneath a Graph-CoT-aware serving layer: attention
+ * over a paged KV cache in which several requests ("branches") reference the same
+ * physical blocks for a common graph-context prefix, plus the block copies that the
+ * cache manager's fork and eviction decisions cause.  All four hot calls are
+ * asynchronous on the caller's HIP stream, allocate no device memory, keep no pointer
+ * after they return, never abort and never throw: they return a status code.
+ *
+ * Memory layout (fixed):
+ *   KV pool   bf16, element (blk, p, hkv, t, c) at ((((blk*2+p)*Hkv+hkv)*bs+t)*d+c),
+ *             p = 0 for K, 1 for V; one block is one contiguous slab of 2*Hkv*bs*d*2 bytes.
+ *   Q         bf16 [rows][Hq][d]; decode has one row per request, prefill sum_q rows in
+ *             request order (request r owns rows cu_q_lens[r] .. cu_q_lens[r+1]-1).
+ *   out       fp32, same shape as Q.
+ *   tables    int32 [B][max_blocks]: logical block index -> physical block id.  Entries at
+ *             or beyond ceil(seq_len/bs) are ignored (may be -1).
+ *   seq_lens  int32 [B]: tokens whose K/V are in the cache, INCLUDING the tokens being
+ *             attended from (the caller appends K/V before calling).
+ * Every pointer named *_dev is device memory, *_host is host memory; `hip_stream` is a
+ * hipStream_t passed as void* (NULL = the null stream).
+ *
+ * Supported geometry: block_size 16; head_dim 64 or 128; num_q_heads a multiple of
+ * num_kv_heads (q head h reads kv head h / (Hq/Hkv)).
+ */
+#ifndef GLM_H_
+#define GLM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GLM_API __attribute__((visibility("default")))
+
+typedef struct {
+    int32_t num_blocks;   /* physical blocks in the pool */
+    int32_t block_size;   /* tokens per block */
+    int32_t num_kv_heads; /* Hkv */
+    int32_t num_q_heads;  /* Hq */
+    int32_t head_dim;     /* d */
+} glm_geom;
+
+enum {
+    GLM_OK = 0,
+    GLM_ERR_NULL = -1,          /* a required pointer is NULL */
+    GLM_ERR_GEOM = -2,          /* non-positive size, Hq % Hkv != 0, unsupported head_dim / block_size */
+    GLM_ERR_ALIGN = -3,         /* pool / q / out / workspace not 16-byte aligned */
+    GLM_ERR_WORKSPACE = -4,     /* workspace missing or too small */
+    GLM_ERR_PLAN_MISMATCH = -5, /* plan built for another B / max_blocks / geometry / call kind */
+    GLM_ERR_RANGE = -6,         /* only with GLM_VALIDATE=1: an id, length or list violates a precondition */
+    GLM_ERR_HIP = -7,           /* a HIP call failed; glm_last_hip_error() has its code */
+    GLM_ERR_ALLOC = -8          /* host allocation failed */
+};
+
+typedef struct glm_plan glm_plan;
+
+/*
+ * Decode attention (paper Sec. 2.4: decoding extends the cache one token at a time and
+ * attends over everything cached; prefix caching lets requests with an identical prefix
+ * reference the same cached blocks without changing outputs).
+ *
+ * For every request r and q head h:  out[r,h,:] = softmax_j(scale * <q[r,h,:], k_j>) . v_j over
+ * the keys j = 0 .. seq_lens[r]-1 reached through block_tables[r]; seq_lens[r] == 0 gives zeros.
+ *
+ *   kv_pool_dev        pool as laid out above (read only during the call)
+ *   q_dev              bf16 [B][Hq][d]
+ *   out_dev            fp32 [B][Hq][d], fully overwritten
+ *   plan               NULL, or a plan made by glm_plan_create for exactly these tables with
+ *                      q_lens_host == NULL.  A plan only changes speed: it lets one workgroup
+ *                      stream a shared block once for all branches grouped on it.  It stays
+ *                      valid while the tables only grow by appending blocks to a request's
+ *                      private tail and seq_lens only grow; any other table change needs a new plan.
+ *   workspace_dev      scratch for split-K partial results; at least
+ *                      glm_plan_workspace_bytes(plan), or without a plan any size from
+ *                      glm_attn_workspace_bytes(g, B, 0, 1) upwards (more allows more splits;
+ *                      glm_attn_workspace_bytes with the real bound is the recommended size)
+ * Errors: NULL / GEOM / ALIGN / WORKSPACE / PLAN_MISMATCH / HIP; RANGE under GLM_VALIDATE=1
+ * (block id outside the pool, seq_len > max_blocks*bs; needs a device-to-host copy and a sync).
+ * B == 0 returns GLM_OK without a launch.
+ */
+GLM_API int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,
+                    const int32_t *block_tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev,
+                    int32_t B, float scale, const glm_plan *plan, void *workspace_dev,
+                    size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Prefill of new tokens on top of a cached prefix (paper Sec. 2.4: prefill processes the
+ * input and fills the cache; Sec. 5.2 case study: when the earlier context is still cached only
+ * the new part is inserted).  Request r has q_len_r = cu_q_lens[r+1]-cu_q_lens[r] new tokens
+ * whose K/V the caller has already written to the pool at positions ctx_r .. seq_lens[r]-1,
+ * ctx_r = seq_lens[r] - q_len_r.  New token i attends keys 0 .. ctx_r + i (all of the cached
+ * prefix, causal inside the new part).  Decode is the case q_len_r = 1.
+ *
+ *   q_dev / out_dev    bf16 / fp32 [sum_q][Hq][d]
+ *   cu_q_lens_dev      int32 [B+1], cu_q_lens[0] = 0, cu_q_lens[B] = sum_q
+ *   max_q_len          upper bound of q_len_r (sizes the launch when there is no plan)
+ *   plan               NULL or a plan made with q_lens_host != NULL for these lengths
+ *   workspace_dev      not used by this call at present (may be NULL)
+ * Errors as for glm_attn_decode; RANGE also covers q_len > seq_len and a cu_q_lens that does
+ * not end at sum_q.  B == 0 or sum_q == 0 returns GLM_OK without a launch.
+ */
+GLM_API int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,
+                               const int32_t *block_tables_dev, int32_t max_blocks,
+                               const int32_t *seq_lens_dev, const int32_t *cu_q_lens_dev, int32_t B,
+                               int32_t sum_q, int32_t max_q_len, float scale, const glm_plan *plan,
+                               void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Fork / copy-on-write copy (a branch that diverges inside a partly filled block needs its
+ * own copy of the rows filled so far; full prefix blocks stay shared - paper Sec. 2.4, 5.1).
+ * For each pair k: the first n_tokens[k] token rows of every (plane, kv head) of block
+ * src_ids[k] are copied to block dst_ids[k] of the same pool.  All other bytes of the pool,
+ * including the remaining rows of the destination blocks, are left unchanged.
+ * Preconditions (checked only under GLM_VALIDATE=1 -> GLM_ERR_RANGE): ids inside the pool,
+ * 0 <= n_tokens <= block_size, destinations distinct and not also sources.  One source may
+ * feed many destinations.  n_pairs == 0 returns GLM_OK without a launch.
+ */
+GLM_API int glm_kv_fork_copy(glm_geom g, void *kv_pool_dev, const int32_t *src_ids_dev, const int32_t *dst_ids_dev,
+                     const int32_t *n_tokens_dev, int32_t n_pairs, void *hip_stream);
+
+/*
+ * Whole-block gather between two buffers with the pool's block geometry (what eviction to a
+ * staging area and later re-admission into other free slots move - paper Sec. 5.2):
+ *     dst_base[dst_ids[k]] = src_base[src_ids[k]]   for k = 0 .. n-1, bit exact.
+ * A NULL id list stands for 0, 1, .., n-1 (pack contiguously / unpack in order).  g.num_blocks
+ * is not used to bound either buffer: the caller guarantees every id lies inside its buffer.
+ * Preconditions (GLM_VALIDATE=1 -> GLM_ERR_RANGE): ids non-negative, destinations distinct;
+ * src and dst ranges must not overlap.  n == 0 returns GLM_OK without a launch.
+ */
+GLM_API int glm_kv_gather(glm_geom g, const void *src_base_dev, const int32_t *src_ids_dev, void *dst_base_dev,
+                  const int32_t *dst_ids_dev, int32_t n, void *hip_stream);
+
+/*
+ * Plan: derived on the host from the block tables.  Maximal runs of logical blocks that the
+ * same set of requests reference through identical physical ids become shared segments
+ * (a prefix tree: agent template -> graph context -> private suffix, paper Sec. 5.2); the plan
+ * holds the work list (segment x token chunk x row tile) and each request's merge list.
+ * q_lens_host == NULL makes a decode plan, otherwise a prefill plan.
+ * glm_plan_create copies the lists to the device (one allocation, owned by the plan, uploaded
+ * on hip_stream) and returns NULL with *status set on failure.  glm_plan_create_host builds
+ * the same plan without touching any device (for inspection; attention calls reject it).
+ */
+GLM_API glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
+                          const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B,
+                          void *hip_stream, int *status);
+GLM_API glm_plan *glm_plan_create_host(glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
+                               const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B,
+                               int *status);
+GLM_API void glm_plan_destroy(glm_plan *plan);
+GLM_API size_t glm_plan_workspace_bytes(const glm_plan *plan);
+
+/* One entry of a plan's work list, for inspection and tests. */
+typedef struct {
+    int32_t rep;      /* request whose block table is walked */
+    int32_t b0, b1;   /* logical blocks [b0, b1); b1 = INT32_MAX: to the end of the members' sequences */
+    int32_t mem_off;  /* decode: offset of the member list; prefill: unused */
+    int32_t n_mem;    /* decode: member requests; prefill: new tokens of rep; 0 = padding entry */
+    int32_t row0;     /* first of the n_mem*(Hq/Hkv) rows this workgroup handles */
+    int32_t slot0;    /* first partial-result slot, or -1: writes the final output itself */
+    int32_t waves;    /* waves per workgroup (16 rows each) */
+} glm_chunk;
+
+GLM_API int32_t glm_plan_num_chunks(const glm_plan *plan);
+GLM_API int32_t glm_plan_get_chunks(const glm_plan *plan, glm_chunk *out, int32_t capacity);
+GLM_API int32_t glm_plan_num_members(const glm_plan *plan);
+GLM_API int32_t glm_plan_get_members(const glm_plan *plan, int32_t *out, int32_t capacity);
+/* number of shared segments (runs referenced by >= 2 requests) and the blocks they cover */
+GLM_API int32_t glm_plan_num_shared_segments(const glm_plan *plan);
+GLM_API int64_t glm_plan_shared_blocks(const glm_plan *plan);
+
+/* Recommended workspace for plan-less calls on up to B requests of up to max_seq_len tokens. */
+GLM_API size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, int32_t max_seq_len);
+
+GLM_API const char *glm_status_string(int status);
+GLM_API int glm_version(void);
+GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLM_H_ */

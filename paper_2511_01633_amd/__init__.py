@@ -1,0 +1,12 @@
+"""Shared-prefix paged-KV attention for MI355X: thin Python binding over libglm.so.
+
+The compute lives in hand-written HIP kernels behind the C ABI of include/glm.h; this
+package only marshals arguments.  Importing it without a built library raises ImportError.
+"""
+from .binding import *  # noqa: F401,F403
+from .binding import (  # noqa: F401
+    GlmError, Plan, glm_geom, glm_chunk, geom, LIB_PATH, EXPORTS,
+    glm_attn_decode, glm_attn_prefill_on_prefix, glm_kv_fork_copy, glm_kv_gather,
+    glm_plan_create, glm_plan_create_host, glm_attn_workspace_bytes,
+    glm_status_string, glm_version, glm_last_hip_error,
+)

@@ -1,0 +1,246 @@
+"""ctypes binding of libglm.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in include/glm.h and
+takes torch tensors (device memory) or raw integer addresses where the header says *_dev,
+numpy int32 arrays where it says *_host.  Nothing is computed here, and there is no
+fallback: if the library has not been built the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libglm.so")
+
+GLM_OK = 0
+GLM_ERR_NULL, GLM_ERR_GEOM, GLM_ERR_ALIGN, GLM_ERR_WORKSPACE = -1, -2, -3, -4
+GLM_ERR_PLAN_MISMATCH, GLM_ERR_RANGE, GLM_ERR_HIP, GLM_ERR_ALLOC = -5, -6, -7, -8
+
+EXPORTS = (
+    "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather",
+    "glm_plan_create", "glm_plan_create_host", "glm_plan_destroy", "glm_plan_workspace_bytes",
+    "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
+    "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
+    "glm_status_string", "glm_version", "glm_last_hip_error",
+)
+
+
+class glm_geom(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("num_blocks", "block_size", "num_kv_heads", "num_q_heads", "head_dim")]
+
+
+class glm_chunk(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("rep", "b0", "b1", "mem_off", "n_mem", "row0", "slot0", "waves")]
+
+
+class GlmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, glm_status_string(status), status))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libglm.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "or `python paper_2511_01633_amd/build.py` (needs hipcc)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    lib.glm_attn_decode.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp, i32, f32, vp, vp, sz, vp]
+    lib.glm_attn_decode.restype = ctypes.c_int
+    lib.glm_attn_prefill_on_prefix.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, f32, vp, vp, sz, vp]
+    lib.glm_attn_prefill_on_prefix.restype = ctypes.c_int
+    lib.glm_kv_fork_copy.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
+    lib.glm_kv_fork_copy.restype = ctypes.c_int
+    lib.glm_kv_gather.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
+    lib.glm_kv_gather.restype = ctypes.c_int
+    lib.glm_plan_create.argtypes = [glm_geom, vp, i32, vp, vp, i32, vp, ctypes.POINTER(ctypes.c_int)]
+    lib.glm_plan_create.restype = vp
+    lib.glm_plan_create_host.argtypes = [glm_geom, vp, i32, vp, vp, i32, ctypes.POINTER(ctypes.c_int)]
+    lib.glm_plan_create_host.restype = vp
+    lib.glm_plan_destroy.argtypes = [vp]
+    lib.glm_plan_destroy.restype = None
+    lib.glm_plan_workspace_bytes.argtypes = [vp]
+    lib.glm_plan_workspace_bytes.restype = sz
+    for n in ("glm_plan_num_chunks", "glm_plan_num_members", "glm_plan_num_shared_segments"):
+        getattr(lib, n).argtypes = [vp]
+        getattr(lib, n).restype = i32
+    lib.glm_plan_shared_blocks.argtypes = [vp]
+    lib.glm_plan_shared_blocks.restype = ctypes.c_int64
+    lib.glm_plan_get_chunks.argtypes = [vp, ctypes.POINTER(glm_chunk), i32]
+    lib.glm_plan_get_chunks.restype = i32
+    lib.glm_plan_get_members.argtypes = [vp, vp, i32]
+    lib.glm_plan_get_members.restype = i32
+    lib.glm_attn_workspace_bytes.argtypes = [glm_geom, i32, i32, i32]
+    lib.glm_attn_workspace_bytes.restype = sz
+    lib.glm_status_string.argtypes = [ctypes.c_int]
+    lib.glm_status_string.restype = ctypes.c_char_p
+    lib.glm_version.restype = ctypes.c_int
+    lib.glm_last_hip_error.restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def geom(g) -> glm_geom:
+    """Accepts a glm_geom or any object with the five geometry attributes."""
+    if isinstance(g, glm_geom):
+        return g
+    return glm_geom(int(g.num_blocks), int(g.block_size), int(g.num_kv_heads), int(g.num_q_heads), int(g.head_dim))
+
+
+def _dev(x) -> Optional[int]:
+    """Device address of a torch tensor (or a raw int address, or None)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _host_i32(x) -> Optional[np.ndarray]:
+    if x is None:
+        return None
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def _nbytes(t) -> int:
+    if t is None:
+        return 0
+    return int(t.numel() * t.element_size())
+
+
+def glm_status_string(status: int) -> str:
+    return _lib.glm_status_string(int(status)).decode()
+
+
+def glm_version() -> int:
+    return int(_lib.glm_version())
+
+
+def glm_last_hip_error() -> int:
+    return int(_lib.glm_last_hip_error())
+
+
+def glm_attn_workspace_bytes(g, B: int, sum_q: int, max_seq_len: int) -> int:
+    return int(_lib.glm_attn_workspace_bytes(geom(g), B, sum_q, max_seq_len))
+
+
+class Plan:
+    """Owns a glm_plan*; destroyed with the object."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            _lib.glm_plan_destroy(self.handle)
+            self.handle = None
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(_lib.glm_plan_workspace_bytes(self.handle))
+
+    @property
+    def num_shared_segments(self) -> int:
+        return int(_lib.glm_plan_num_shared_segments(self.handle))
+
+    @property
+    def shared_blocks(self) -> int:
+        return int(_lib.glm_plan_shared_blocks(self.handle))
+
+    def chunks(self):
+        n = int(_lib.glm_plan_num_chunks(self.handle))
+        arr = (glm_chunk * max(n, 1))()
+        n = int(_lib.glm_plan_get_chunks(self.handle, arr, n))
+        return [arr[i] for i in range(n)]
+
+    def members(self) -> np.ndarray:
+        n = int(_lib.glm_plan_num_members(self.handle))
+        out = np.zeros(max(n, 1), np.int32)
+        n = int(_lib.glm_plan_get_members(self.handle, _hp(out), n))
+        return out[:n]
+
+
+def glm_plan_create(g, block_tables_host, max_blocks: int, seq_lens_host, q_lens_host, B: int, hip_stream=None) -> Plan:
+    bt, sl, ql = _host_i32(block_tables_host), _host_i32(seq_lens_host), _host_i32(q_lens_host)
+    st = ctypes.c_int(0)
+    h = _lib.glm_plan_create(geom(g), _hp(bt), max_blocks, _hp(sl), _hp(ql), B, _stream(hip_stream), ctypes.byref(st))
+    if not h:
+        raise GlmError(st.value, "glm_plan_create")
+    return Plan(h)
+
+
+def glm_plan_create_host(g, block_tables_host, max_blocks: int, seq_lens_host, q_lens_host, B: int) -> Plan:
+    bt, sl, ql = _host_i32(block_tables_host), _host_i32(seq_lens_host), _host_i32(q_lens_host)
+    st = ctypes.c_int(0)
+    h = _lib.glm_plan_create_host(geom(g), _hp(bt), max_blocks, _hp(sl), _hp(ql), B, ctypes.byref(st))
+    if not h:
+        raise GlmError(st.value, "glm_plan_create_host")
+    return Plan(h)
+
+
+def _check(status: int, where: str) -> None:
+    if status != GLM_OK:
+        raise GlmError(status, where)
+
+
+def glm_attn_decode(g, kv_pool_dev, q_dev, out_dev, block_tables_dev, max_blocks: int, seq_lens_dev, B: int,
+                    scale: float, plan: Optional[Plan] = None, workspace_dev=None, workspace_bytes: Optional[int] = None,
+                    hip_stream=None, check: bool = True) -> int:
+    wb = _nbytes(workspace_dev) if workspace_bytes is None else workspace_bytes
+    st = _lib.glm_attn_decode(geom(g), _dev(kv_pool_dev), _dev(q_dev), _dev(out_dev), _dev(block_tables_dev),
+                              max_blocks, _dev(seq_lens_dev), B, scale, plan.handle if plan else None,
+                              _dev(workspace_dev), wb, _stream(hip_stream))
+    if check:
+        _check(st, "glm_attn_decode")
+    return st
+
+
+def glm_attn_prefill_on_prefix(g, kv_pool_dev, q_dev, out_dev, block_tables_dev, max_blocks: int, seq_lens_dev,
+                               cu_q_lens_dev, B: int, sum_q: int, max_q_len: int, scale: float,
+                               plan: Optional[Plan] = None, workspace_dev=None, workspace_bytes: Optional[int] = None,
+                               hip_stream=None, check: bool = True) -> int:
+    wb = _nbytes(workspace_dev) if workspace_bytes is None else workspace_bytes
+    st = _lib.glm_attn_prefill_on_prefix(geom(g), _dev(kv_pool_dev), _dev(q_dev), _dev(out_dev),
+                                         _dev(block_tables_dev), max_blocks, _dev(seq_lens_dev), _dev(cu_q_lens_dev),
+                                         B, sum_q, max_q_len, scale, plan.handle if plan else None,
+                                         _dev(workspace_dev), wb, _stream(hip_stream))
+    if check:
+        _check(st, "glm_attn_prefill_on_prefix")
+    return st
+
+
+def glm_kv_fork_copy(g, kv_pool_dev, src_ids_dev, dst_ids_dev, n_tokens_dev, n_pairs: int, hip_stream=None,
+                     check: bool = True) -> int:
+    st = _lib.glm_kv_fork_copy(geom(g), _dev(kv_pool_dev), _dev(src_ids_dev), _dev(dst_ids_dev), _dev(n_tokens_dev),
+                               n_pairs, _stream(hip_stream))
+    if check:
+        _check(st, "glm_kv_fork_copy")
+    return st
+
+
+def glm_kv_gather(g, src_base_dev, src_ids_dev, dst_base_dev, dst_ids_dev, n: int, hip_stream=None,
+                  check: bool = True) -> int:
+    st = _lib.glm_kv_gather(geom(g), _dev(src_base_dev), _dev(src_ids_dev), _dev(dst_base_dev), _dev(dst_ids_dev), n,
+                            _stream(hip_stream))
+    if check:
+        _check(st, "glm_kv_gather")
+    return st

@@ -1,0 +1,583 @@
+// Attention over a paged KV cache with shared prefix blocks: the streaming kernel, the
+// split-K merge kernel and the two C entry points (decode, prefill on a cached prefix).
+//
+// One kernel serves both calls.  A workgroup owns one work item: a run of logical blocks of
+// one representative request's table, one kv head, and up to 16*W query rows that all see
+// that run - the G = Hq/Hkv heads of every member request (decode) or of consecutive new
+// tokens (prefill).  K/V tiles of two blocks (32 tokens) are loaded once with coalesced
+// 16-byte loads, staged in LDS and shared by the W waves; each wave keeps 16 rows.
+//
+// Everything is computed transposed so that a query row lives in one lane column:
+//   S^T[token][row] = K . Q^T      v_mfma_f32_16x16x32_bf16, A = K rows read from LDS,
+//                                  B = Q^T held in registers for the whole item
+//   running max / sum per row      the 4 lanes that share a row exchange through two shuffles
+//   O^T[d][row]    += V^T . P^T    A = V^T through the LDS transpose read (ds_read_b64_tr_b16),
+//                                  B = P^T, which is exactly the register layout S^T came out in
+// P is split into a bf16 head and a bf16 remainder (two MFMAs) so that the weights keep
+// ~16 bits; the row sum is taken from the same rounded values.
+#include <cmath>
+#include <cstdlib>
+#include <vector>
+
+#include "glm_internal.h"
+
+namespace glm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+enum AttnMode : int32_t { kPlanned = 0, kImplicitDecode = 1, kImplicitPrefill = 2 };
+
+struct AttnArgs {
+    const __bf16 *pool;
+    const __bf16 *q;
+    float *out;
+    const int32_t *tables;
+    const int32_t *seq_lens;
+    const int32_t *cu_q_lens;   // nullptr: decode
+    const glm_chunk *chunks;    // planned mode
+    const int32_t *members;     // planned decode
+    float *part_ml;             // [slot][Hq][2]  (running max in log2 units, sum)
+    float *part_acc;            // [slot][Hq][D]
+    int32_t max_blocks, B, Hkv, Hq, G, num_blocks;
+    int32_t mode;
+    int32_t n_split, chunk_blocks, row_tiles;   // implicit modes
+    float scale_log2;           // scale * log2(e)
+};
+
+struct MergeArgs {
+    const float *part_ml;
+    const float *part_acc;
+    float *out;
+    const int32_t *seq_lens;
+    const int32_t *merge_off, *merge_slots, *merge_kind;   // nullptr: implicit
+    int32_t Hq, max_blocks, n_split, chunk_blocks;
+};
+
+__device__ __forceinline__ int wave_max(int v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+}
+
+template <int D, int W>
+__global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
+    constexpr int NT = 64 * W;
+    constexpr int KSTR = D + 8;            // LDS row pitch of K in elements (16 B pad: conflict-free b128 row reads)
+    constexpr int VSTR = D + 16;           // LDS row pitch of V (32 B pad: conflict-free transpose reads)
+    constexpr int PPS = 16 * D / 8;        // 16-byte pieces in one (block, plane, head) slab
+    constexpr int PPT = 4 * PPS / NT;      // pieces per thread per 32-token tile (2 K + 2 V slabs)
+    constexpr int KS = D / 32;             // k-steps of S^T = K.Q^T
+    constexpr int DT = D / 16;             // 16-wide d tiles of O^T
+    static_assert(4 * PPS % NT == 0, "tile must split evenly over the threads");
+
+    __shared__ __attribute__((aligned(16))) __bf16 k_lds[32 * KSTR];
+    __shared__ __attribute__((aligned(16))) __bf16 v_lds[32 * VSTR];
+    __shared__ int wave_lim[W];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n16 = lane & 15;             // row within the wave's 16 rows / token within a block
+    const int g4 = lane >> 4;              // which quarter of the k slots this lane holds
+
+    // ------------------------------------------------------------------ which work item
+    glm_chunk c;
+    int kvh;
+    const int G = a.G;
+    if (a.mode == kPlanned) {
+        const int L = blockIdx.x;
+        const int x = L % kXcds, k = L / kXcds;
+        kvh = k % a.Hkv;
+        c = a.chunks[(k / a.Hkv) * kXcds + x];
+        if (c.n_mem == 0) return;
+    } else if (a.mode == kImplicitDecode) {
+        int L = blockIdx.x;
+        kvh = L % a.Hkv; L /= a.Hkv;
+        const int rt = L % a.row_tiles; L /= a.row_tiles;
+        const int s = L % a.n_split;
+        const int r = L / a.n_split;
+        c.rep = r;
+        c.b0 = s * a.chunk_blocks;
+        c.b1 = (s == a.n_split - 1) ? INT32_MAX : (s + 1) * a.chunk_blocks;
+        c.mem_off = -1;
+        c.n_mem = 1;
+        c.row0 = rt * 16 * W;
+        c.slot0 = r * a.n_split + s;
+        if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
+    } else {
+        int L = blockIdx.x;
+        kvh = L % a.Hkv; L /= a.Hkv;
+        const int t = L % a.row_tiles;
+        const int r = L / a.row_tiles;
+        c.rep = r;
+        c.b0 = 0;
+        c.b1 = INT32_MAX;
+        c.mem_off = -1;
+        c.n_mem = a.cu_q_lens[r + 1] - a.cu_q_lens[r];
+        c.row0 = t * 16 * W;
+        c.slot0 = -1;
+        if (c.row0 >= c.n_mem * G) return;
+    }
+
+    // ------------------------------------------------------------------ this lane's query row
+    const int rho = c.row0 + wave * 16 + n16;
+    const bool valid = rho < c.n_mem * G;
+    const int mi = rho / G, gh = rho - mi * G;
+    int64_t q_row = 0;
+    int limit = 0;
+    if (valid) {
+        if (a.cu_q_lens) {
+            const int ctx = a.seq_lens[c.rep] - c.n_mem;
+            q_row = (int64_t)a.cu_q_lens[c.rep] + mi;
+            limit = ctx + mi + 1;
+        } else {
+            const int r = c.mem_off < 0 ? c.rep : a.members[c.mem_off + mi];
+            q_row = r;
+            limit = a.seq_lens[r];
+        }
+    }
+    const int head = kvh * G + gh;
+
+    int wg_lim = wave_max(limit);
+    if (W > 1) {
+        if (lane == 0) wave_lim[wave] = wg_lim;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < W; ++w) wg_lim = max(wg_lim, wave_lim[w]);
+    }
+    int end_blk = (wg_lim + kBlockSize - 1) / kBlockSize;
+    end_blk = min(min(end_blk, c.b1), a.max_blocks);
+    wg_lim = min(wg_lim, end_blk * kBlockSize);         // nothing at or beyond this position is visible to any row
+    const int lim_eff = min(limit, end_blk * kBlockSize);
+    const int nblk = end_blk - c.b0;
+    const int ntiles = nblk > 0 ? (nblk + 1) >> 1 : 0;
+
+    bf16x8 qreg[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        if (valid) {
+            qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 32 * s + 8 * g4);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
+        }
+    }
+
+    f32x4 acc[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY;
+    float l_run = 0.f;      // this lane's share of the row sum (its 8 of every 32 tokens)
+
+    const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
+    const int64_t slab = (int64_t)kBlockSize * D;                 // elements of one (block, plane, head) slab
+    const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
+    auto phys = [&](int b) -> int64_t {
+        const int bi = min(b, end_blk - 1);
+        const int id = table[bi];
+        return (int64_t)min(max(id, 0), a.num_blocks - 1);
+    };
+
+    u32x4 stage[PPT];
+    auto issue_loads = [&](int64_t idA, int64_t idB) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int gp = tid + NT * i;
+            const int sl = gp / PPS, p = gp % PPS;               // slab 0: K blk A, 1: K blk B, 2: V blk A, 3: V blk B
+            const int64_t id = (sl & 1) ? idB : idA;
+            const __bf16 *src = a.pool + id * blk_elems + ((int64_t)(sl >> 1) * a.Hkv + kvh) * slab + p * 8;
+            stage[i] = *reinterpret_cast<const u32x4 *>(src);
+        }
+    };
+
+    int64_t idA_next = 0, idB_next = 0;
+    if (ntiles > 0) {
+        issue_loads(phys(c.b0), phys(c.b0 + 1));
+        if (ntiles > 1) { idA_next = phys(c.b0 + 2); idB_next = phys(c.b0 + 3); }
+    }
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int pos0 = (c.b0 + 2 * t) * kBlockSize;           // logical position of the tile's first token
+        const bool tail = pos0 + 32 > wg_lim;
+        __syncthreads();                                          // every wave is done reading the previous tile
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int gp = tid + NT * i;
+            const int sl = gp / PPS, p = gp % PPS;
+            const int tok = p / (D / 8), ch = p % (D / 8);
+            const int row = (sl & 1) * 16 + tok;
+            u32x4 v = stage[i];
+            if (sl >= 2) {
+                // V rows no query row can see must be finite: their weight is 0 and 0 * NaN is NaN
+                if (tail && pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(&v_lds[row * VSTR + ch * 8]) = v;
+            } else {
+                *reinterpret_cast<u32x4 *>(&k_lds[row * KSTR + ch * 8]) = v;
+            }
+        }
+        __syncthreads();
+        if (t + 1 < ntiles) {
+            issue_loads(idA_next, idB_next);
+            if (t + 2 < ntiles) { idA_next = phys(c.b0 + 2 * t + 4); idB_next = phys(c.b0 + 2 * t + 5); }
+        }
+
+        // ---- S^T = K . Q^T for the two blocks of the tile
+        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&k_lds[n16 * KSTR + 32 * ks + 8 * g4]);
+            const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(&k_lds[(16 + n16) * KSTR + 32 * ks + 8 * g4]);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qreg[ks], s1, 0, 0, 0);
+        }
+        // lane (row n16, quarter g4) now holds tokens 4*g4+i of block A in s0[i] and of block B in s1[i]
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = s0[i] * a.scale_log2; x[4 + i] = s1[i] * a.scale_log2; }
+        if (pos0 + 32 > lim_eff) {                                // this row's visible range ends inside the tile
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (pos0 + 4 * g4 + i >= lim_eff) x[i] = -INFINITY;
+                if (pos0 + 16 + 4 * g4 + i >= lim_eff) x[4 + i] = -INFINITY;
+            }
+        }
+        float m_tile = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        const float m_new = fmaxf(m_run, m_tile);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        bf16x8 p_hi, p_lo;
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float p = __builtin_amdgcn_exp2f(x[j] - m_use);
+            const __bf16 h = (__bf16)p;
+            const float hf = (float)h;
+            const __bf16 l = (__bf16)(p - hf);
+            p_hi[j] = h;
+            p_lo[j] = l;
+            psum += hf + (float)l;
+        }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) acc[dt] *= alpha;
+
+        // ---- O^T += V^T . P^T
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const __bf16 *va = &v_lds[(4 * g4 + (n16 >> 2)) * VSTR + 16 * dt + 4 * (n16 & 3)];
+            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(va));
+            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(va + 16 * VSTR));
+            const s16x8 r01 = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 vt = __builtin_bit_cast(bf16x8, r01);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, acc[dt], 0, 0, 0);
+        }
+    }
+
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (!valid) return;
+    if (c.slot0 >= 0) {
+        const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
+        if (g4 == 0) {
+            a.part_ml[slot * 2] = m_run;
+            a.part_ml[slot * 2 + 1] = l_run;
+        }
+        float *dst = a.part_acc + slot * D + 4 * g4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt];
+    } else {
+        const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+        float *dst = a.out + (q_row * a.Hq + head) * D + 4 * g4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt] * inv;
+    }
+}
+
+// Combines a request's partial results in list order:
+//   M = max m_i,  l = sum l_i 2^(m_i-M),  out = sum acc_i 2^(m_i-M) / l.
+template <int D>
+__global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
+    const int r = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
+    const int tid = threadIdx.x;
+    constexpr int E = D / 64;
+    float *dst = a.out + ((int64_t)r * a.Hq + h) * D + tid * E;
+    int n, first = 0;
+    const int32_t *slots = nullptr;
+    if (a.merge_kind) {
+        const int kind = a.merge_kind[r];
+        if (kind == kMergeDirect) return;
+        if (kind == kMergeZero) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) dst[e] = 0.f;
+            return;
+        }
+        slots = a.merge_slots + a.merge_off[r];
+        n = a.merge_off[r + 1] - a.merge_off[r];
+    } else {
+        const int nb = min((a.seq_lens[r] + kBlockSize - 1) / kBlockSize, a.max_blocks);
+        n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
+        first = r * a.n_split;
+    }
+    float M = -INFINITY;
+    for (int i = 0; i < n; ++i) {
+        const int64_t s = ((int64_t)(slots ? slots[i] : first + i)) * a.Hq + h;
+        M = fmaxf(M, a.part_ml[s * 2]);
+    }
+    float l = 0.f, o[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = 0.f;
+    if (M != -INFINITY) {
+        for (int i = 0; i < n; ++i) {
+            const int64_t s = ((int64_t)(slots ? slots[i] : first + i)) * a.Hq + h;
+            const float w = __builtin_amdgcn_exp2f(a.part_ml[s * 2] - M);
+            l += a.part_ml[s * 2 + 1] * w;
+            const float *src = a.part_acc + s * D + tid * E;
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] += src[e] * w;
+        }
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) dst[e] = o[e] * inv;
+}
+
+// ------------------------------------------------------------------------------------ host side
+
+static thread_local int g_last_hip_error = 0;
+
+int set_hip_error(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return GLM_ERR_HIP;
+}
+
+bool validate_enabled() {
+    const char *s = std::getenv("GLM_VALIDATE");
+    return s && s[0] == '1';
+}
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <int W>
+hipError_t launch_stream(int D, const AttnArgs &args, int grid, hipStream_t st) {
+    if (grid <= 0) return hipSuccess;
+    if (D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, W>), dim3(grid), dim3(64 * W), 0, st, args);
+    else hipLaunchKernelGGL((attn_stream_kernel<64, W>), dim3(grid), dim3(64 * W), 0, st, args);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(int D, const MergeArgs &m, int grid, hipStream_t st) {
+    if (grid <= 0) return hipSuccess;
+    if (D == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(grid), dim3(64), 0, st, m);
+    else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(grid), dim3(64), 0, st, m);
+    return hipGetLastError();
+}
+
+// Debug-only range checks on the device inputs (GLM_VALIDATE=1): copies them back and syncs.
+int validate_inputs(const glm_geom &g, const int32_t *tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev,
+                    const int32_t *cu_dev, int32_t B, int32_t sum_q, hipStream_t st) {
+    try {
+        std::vector<int32_t> tables((size_t)B * max_blocks), lens(B), cu(cu_dev ? B + 1 : 0);
+        hipError_t e = hipStreamSynchronize(st);
+        if (e == hipSuccess) e = hipMemcpy(tables.data(), tables_dev, tables.size() * 4, hipMemcpyDeviceToHost);
+        if (e == hipSuccess) e = hipMemcpy(lens.data(), seq_lens_dev, lens.size() * 4, hipMemcpyDeviceToHost);
+        if (e == hipSuccess && cu_dev) e = hipMemcpy(cu.data(), cu_dev, cu.size() * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return set_hip_error(e);
+        if (cu_dev && (cu[0] != 0 || cu[B] != sum_q)) return GLM_ERR_RANGE;
+        for (int32_t r = 0; r < B; ++r) {
+            const int64_t L = lens[r];
+            if (L < 0 || L > (int64_t)max_blocks * kBlockSize) return GLM_ERR_RANGE;
+            if (cu_dev) {
+                const int64_t ql = (int64_t)cu[r + 1] - cu[r];
+                if (ql < 0 || ql > L) return GLM_ERR_RANGE;
+            }
+            const int64_t nb = (L + kBlockSize - 1) / kBlockSize;
+            for (int64_t b = 0; b < nb; ++b) {
+                const int32_t id = tables[(size_t)r * max_blocks + b];
+                if (id < 0 || id >= g.num_blocks) return GLM_ERR_RANGE;
+            }
+        }
+    } catch (...) {
+        return GLM_ERR_ALLOC;
+    }
+    return GLM_OK;
+}
+
+}  // namespace
+}  // namespace glm
+
+using namespace glm;
+
+extern "C" {
+
+size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, int32_t max_seq_len) {
+    (void)sum_q;
+    if (check_geom(g) != GLM_OK || B <= 0) return 256;
+    int64_t splits = ((int64_t)std::max(max_seq_len, 1) + 255) / 256;
+    splits = std::min<int64_t>(std::max<int64_t>(splits, 1), kMaxImplicitSplits);
+    return std::max<size_t>(256, (size_t)B * splits * g.num_q_heads * (size_t)(g.head_dim + 2) * sizeof(float));
+}
+
+int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,
+                    const int32_t *block_tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev, int32_t B,
+                    float scale, const glm_plan *plan, void *workspace_dev, size_t workspace_bytes,
+                    void *hip_stream) {
+    if (int st = check_geom(g)) return st;
+    if (B < 0 || max_blocks <= 0) return GLM_ERR_GEOM;
+    if (B == 0) return GLM_OK;
+    if (!kv_pool_dev || !q_dev || !out_dev || !block_tables_dev || !seq_lens_dev) return GLM_ERR_NULL;
+    if (!aligned16(kv_pool_dev) || !aligned16(q_dev) || !aligned16(out_dev) || !aligned16(workspace_dev))
+        return GLM_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int D = g.head_dim, Hq = g.num_q_heads, Hkv = g.num_kv_heads, G = Hq / Hkv;
+    const size_t slot_bytes = (size_t)Hq * (D + 2) * sizeof(float);
+
+    AttnArgs a{};
+    a.pool = (const __bf16 *)kv_pool_dev;
+    a.q = (const __bf16 *)q_dev;
+    a.out = (float *)out_dev;
+    a.tables = block_tables_dev;
+    a.seq_lens = seq_lens_dev;
+    a.cu_q_lens = nullptr;
+    a.max_blocks = max_blocks; a.B = B; a.Hkv = Hkv; a.Hq = Hq; a.G = G; a.num_blocks = g.num_blocks;
+    a.scale_log2 = scale * 1.44269504088896340736f;
+
+    MergeArgs m{};
+    m.out = (float *)out_dev;
+    m.seq_lens = seq_lens_dev;
+    m.Hq = Hq; m.max_blocks = max_blocks;
+
+    size_t n_slots;
+    if (plan) {
+        if (plan->kind != kDecode || plan->B != B || plan->max_blocks != max_blocks || !plan->dev ||
+            plan->g.num_q_heads != Hq || plan->g.num_kv_heads != Hkv || plan->g.head_dim != D ||
+            plan->g.num_blocks != g.num_blocks)
+            return GLM_ERR_PLAN_MISMATCH;
+        n_slots = (size_t)plan->n_slots;
+    } else {
+        if (!workspace_dev || workspace_bytes < slot_bytes * (size_t)B) return GLM_ERR_WORKSPACE;
+        int64_t splits = std::min<int64_t>((int64_t)(workspace_bytes / (slot_bytes * (size_t)B)), kMaxImplicitSplits);
+        splits = std::min<int64_t>(splits, ((int64_t)max_blocks * kBlockSize + 255) / 256);
+        splits = std::max<int64_t>(splits, 1);
+        int32_t cb = (int32_t)((max_blocks + splits - 1) / splits);
+        cb = (cb + 1) & ~1;
+        a.n_split = (int32_t)((max_blocks + cb - 1) / cb);
+        a.chunk_blocks = cb;
+        n_slots = (size_t)B * a.n_split;
+    }
+    if (n_slots > 0 && (!workspace_dev || workspace_bytes < n_slots * slot_bytes)) return GLM_ERR_WORKSPACE;
+    a.part_ml = (float *)workspace_dev;
+    a.part_acc = a.part_ml + n_slots * (size_t)Hq * 2;
+    m.part_ml = a.part_ml;
+    m.part_acc = a.part_acc;
+
+    if (validate_enabled())
+        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, nullptr, B, 0, st)) return v;
+
+    hipError_t e = hipSuccess;
+    if (plan) {
+        a.mode = kPlanned;
+        a.members = plan->d.members;
+        a.chunks = plan->d.chunks[1];
+        e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
+        if (e == hipSuccess) {
+            a.chunks = plan->d.chunks[0];
+            e = launch_stream<1>(D, a, plan->d.n_chunks[0] * Hkv, st);
+        }
+        m.merge_off = plan->d.merge_off;
+        m.merge_slots = plan->d.merge_slots;
+        m.merge_kind = plan->d.merge_kind;
+    } else {
+        a.mode = kImplicitDecode;
+        if (G > kRowsPerWave) {
+            a.row_tiles = (G + kRowsPerWave * kBigWaves - 1) / (kRowsPerWave * kBigWaves);
+            e = launch_stream<kBigWaves>(D, a, B * a.n_split * a.row_tiles * Hkv, st);
+        } else {
+            a.row_tiles = 1;
+            e = launch_stream<1>(D, a, B * a.n_split * Hkv, st);
+        }
+        m.n_split = a.n_split;
+        m.chunk_blocks = a.chunk_blocks;
+    }
+    if (e == hipSuccess) e = launch_merge(D, m, B * Hq, st);
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,
+                               const int32_t *block_tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev,
+                               const int32_t *cu_q_lens_dev, int32_t B, int32_t sum_q, int32_t max_q_len, float scale,
+                               const glm_plan *plan, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace_dev; (void)workspace_bytes;
+    if (int st = check_geom(g)) return st;
+    if (B < 0 || max_blocks <= 0 || sum_q < 0 || max_q_len < 0) return GLM_ERR_GEOM;
+    if (B == 0 || sum_q == 0) return GLM_OK;
+    if (!kv_pool_dev || !q_dev || !out_dev || !block_tables_dev || !seq_lens_dev || !cu_q_lens_dev) return GLM_ERR_NULL;
+    if (!aligned16(kv_pool_dev) || !aligned16(q_dev) || !aligned16(out_dev)) return GLM_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int D = g.head_dim, Hq = g.num_q_heads, Hkv = g.num_kv_heads, G = Hq / Hkv;
+    if (plan && (plan->kind != kPrefill || plan->B != B || plan->max_blocks != max_blocks || !plan->dev ||
+                 plan->g.num_q_heads != Hq || plan->g.num_kv_heads != Hkv || plan->g.head_dim != D ||
+                 plan->g.num_blocks != g.num_blocks))
+        return GLM_ERR_PLAN_MISMATCH;
+
+    AttnArgs a{};
+    a.pool = (const __bf16 *)kv_pool_dev;
+    a.q = (const __bf16 *)q_dev;
+    a.out = (float *)out_dev;
+    a.tables = block_tables_dev;
+    a.seq_lens = seq_lens_dev;
+    a.cu_q_lens = cu_q_lens_dev;
+    a.max_blocks = max_blocks; a.B = B; a.Hkv = Hkv; a.Hq = Hq; a.G = G; a.num_blocks = g.num_blocks;
+    a.scale_log2 = scale * 1.44269504088896340736f;
+
+    if (validate_enabled())
+        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, cu_q_lens_dev, B, sum_q, st)) return v;
+
+    hipError_t e;
+    if (plan) {
+        a.mode = kPlanned;
+        a.chunks = plan->d.chunks[1];
+        e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
+    } else {
+        if (max_q_len == 0) return GLM_OK;
+        a.mode = kImplicitPrefill;
+        const int64_t tiles = ((int64_t)max_q_len * G + kRowsPerWave * kBigWaves - 1) / (kRowsPerWave * kBigWaves);
+        const int64_t grid = tiles * B * Hkv;
+        if (grid > INT32_MAX) return GLM_ERR_GEOM;
+        a.row_tiles = (int32_t)tiles;
+        e = launch_stream<kBigWaves>(D, a, (int)grid, st);
+    }
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+const char *glm_status_string(int status) {
+    switch (status) {
+        case GLM_OK: return "ok";
+        case GLM_ERR_NULL: return "a required pointer is NULL";
+        case GLM_ERR_GEOM: return "unsupported or inconsistent geometry";
+        case GLM_ERR_ALIGN: return "a buffer is not 16-byte aligned";
+        case GLM_ERR_WORKSPACE: return "workspace missing or too small";
+        case GLM_ERR_PLAN_MISMATCH: return "plan does not match this call";
+        case GLM_ERR_RANGE: return "an id, length or index list is out of range";
+        case GLM_ERR_HIP: return "a HIP call failed";
+        case GLM_ERR_ALLOC: return "host allocation failed";
+        default: return "unknown status";
+    }
+}
+
+int glm_version(void) { return 100; }
+
+int glm_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+// Block copies driven by the cache manager: copy-on-write of a partly filled block when a
+// branch forks, and whole-block gather for eviction to a staging area / re-admission.
+// Both are pure HBM traffic: 16-byte vector loads and stores, several in flight per lane.
+#include <algorithm>
+#include <vector>
+
+#include "glm_internal.h"
+
+namespace glm {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCopyThreads = 256;
+constexpr int kCopyUnroll = 4;                                   // 16-byte pieces in flight per thread
+constexpr int kCopySpan = kCopyThreads * kCopyUnroll;            // pieces one workgroup moves
+
+// grid = (ceil(pieces_per_block / kCopySpan), n)
+__global__ void __launch_bounds__(kCopyThreads) gather_kernel(const u32x4 *__restrict__ src, const int32_t *__restrict__ src_ids,
+                                                              u32x4 *__restrict__ dst, const int32_t *__restrict__ dst_ids,
+                                                              int64_t pieces_per_block) {
+    const int k = blockIdx.y;
+    const int64_t s = src_ids ? src_ids[k] : k;
+    const int64_t d = dst_ids ? dst_ids[k] : k;
+    const u32x4 *sp = src + s * pieces_per_block;
+    u32x4 *dp = dst + d * pieces_per_block;
+    const int64_t base = (int64_t)blockIdx.x * kCopySpan + threadIdx.x;
+    u32x4 v[kCopyUnroll];
+#pragma unroll
+    for (int i = 0; i < kCopyUnroll; ++i) {
+        const int64_t p = base + (int64_t)i * kCopyThreads;
+        if (p < pieces_per_block) v[i] = __builtin_nontemporal_load(sp + p);
+    }
+#pragma unroll
+    for (int i = 0; i < kCopyUnroll; ++i) {
+        const int64_t p = base + (int64_t)i * kCopyThreads;
+        if (p < pieces_per_block) __builtin_nontemporal_store(v[i], dp + p);
+    }
+}
+
+// grid = (2 * Hkv, n_pairs): one workgroup copies the first n_tokens rows of one (plane, kv head).
+// A row is row_pieces 16-byte pieces and the rows of a (plane, head) slab are contiguous.
+__global__ void __launch_bounds__(kCopyThreads) fork_copy_kernel(u32x4 *__restrict__ pool, const int32_t *__restrict__ src_ids,
+                                                                 const int32_t *__restrict__ dst_ids,
+                                                                 const int32_t *__restrict__ n_tokens, int row_pieces,
+                                                                 int64_t pieces_per_block, int num_blocks) {
+    const int k = blockIdx.y;
+    const int n = min(max(n_tokens[k], 0), kBlockSize);
+    const int64_t s = min(max(src_ids[k], 0), num_blocks - 1);
+    const int64_t d = min(max(dst_ids[k], 0), num_blocks - 1);
+    const int64_t slab = (int64_t)blockIdx.x * kBlockSize * row_pieces;
+    const u32x4 *sp = pool + s * pieces_per_block + slab;
+    u32x4 *dp = pool + d * pieces_per_block + slab;
+    const int total = n * row_pieces;
+    for (int p = threadIdx.x; p < total; p += kCopyThreads) dp[p] = sp[p];
+}
+
+namespace {
+
+int validate_ids(const int32_t *ids_dev, int32_t n, int64_t upper, bool distinct, std::vector<int32_t> *keep,
+                 hipStream_t st) {
+    if (!ids_dev) return GLM_OK;
+    try {
+        std::vector<int32_t> h(n);
+        hipError_t e = hipStreamSynchronize(st);
+        if (e == hipSuccess) e = hipMemcpy(h.data(), ids_dev, (size_t)n * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return set_hip_error(e);
+        for (int32_t v : h)
+            if (v < 0 || (upper >= 0 && v >= upper)) return GLM_ERR_RANGE;
+        if (keep) *keep = h;
+        if (distinct) {
+            std::sort(h.begin(), h.end());
+            if (std::adjacent_find(h.begin(), h.end()) != h.end()) return GLM_ERR_RANGE;
+        }
+    } catch (...) {
+        return GLM_ERR_ALLOC;
+    }
+    return GLM_OK;
+}
+
+}  // namespace
+}  // namespace glm
+
+using namespace glm;
+
+extern "C" {
+
+int glm_kv_gather(glm_geom g, const void *src_base_dev, const int32_t *src_ids_dev, void *dst_base_dev,
+                  const int32_t *dst_ids_dev, int32_t n, void *hip_stream) {
+    if (int st = check_geom(g)) return st;
+    if (n < 0) return GLM_ERR_GEOM;
+    if (n == 0) return GLM_OK;
+    if (!src_base_dev || !dst_base_dev) return GLM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(src_base_dev) | reinterpret_cast<uintptr_t>(dst_base_dev)) & 15u) return GLM_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (validate_enabled()) {
+        if (int v = validate_ids(src_ids_dev, n, -1, false, nullptr, st)) return v;
+        if (int v = validate_ids(dst_ids_dev, n, -1, true, nullptr, st)) return v;
+    }
+    const int64_t pieces = 2LL * g.num_kv_heads * g.block_size * g.head_dim * 2 / 16;
+    const int gx = (int)((pieces + kCopySpan - 1) / kCopySpan);
+    for (int32_t done = 0; done < n; done += 65535) {             // grid.y limit
+        const int32_t cnt = std::min<int32_t>(65535, n - done);
+        const int64_t off_s = src_ids_dev ? 0 : (int64_t)done * pieces;
+        const int64_t off_d = dst_ids_dev ? 0 : (int64_t)done * pieces;
+        hipLaunchKernelGGL(gather_kernel, dim3(gx, cnt), dim3(kCopyThreads), 0, st,
+                           (const u32x4 *)src_base_dev + off_s, src_ids_dev ? src_ids_dev + done : nullptr,
+                           (u32x4 *)dst_base_dev + off_d, dst_ids_dev ? dst_ids_dev + done : nullptr, pieces);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return set_hip_error(e);
+    }
+    return GLM_OK;
+}
+
+int glm_kv_fork_copy(glm_geom g, void *kv_pool_dev, const int32_t *src_ids_dev, const int32_t *dst_ids_dev,
+                     const int32_t *n_tokens_dev, int32_t n_pairs, void *hip_stream) {
+    if (int st = check_geom(g)) return st;
+    if (n_pairs < 0) return GLM_ERR_GEOM;
+    if (n_pairs == 0) return GLM_OK;
+    if (!kv_pool_dev || !src_ids_dev || !dst_ids_dev || !n_tokens_dev) return GLM_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(kv_pool_dev) & 15u) return GLM_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (validate_enabled()) {
+        std::vector<int32_t> src, dst;
+        if (int v = validate_ids(src_ids_dev, n_pairs, g.num_blocks, false, &src, st)) return v;
+        if (int v = validate_ids(dst_ids_dev, n_pairs, g.num_blocks, true, &dst, st)) return v;
+        if (int v = validate_ids(n_tokens_dev, n_pairs, g.block_size + 1, false, nullptr, st)) return v;
+        std::sort(src.begin(), src.end());
+        for (int32_t d : dst)
+            if (std::binary_search(src.begin(), src.end(), d)) return GLM_ERR_RANGE;
+    }
+    const int row_pieces = g.head_dim * 2 / 16;
+    const int64_t pieces = 2LL * g.num_kv_heads * g.block_size * row_pieces;
+    for (int32_t done = 0; done < n_pairs; done += 65535) {
+        const int32_t cnt = std::min<int32_t>(65535, n_pairs - done);
+        hipLaunchKernelGGL(fork_copy_kernel, dim3(2 * g.num_kv_heads, cnt), dim3(kCopyThreads), 0, st,
+                           (u32x4 *)kv_pool_dev, src_ids_dev + done, dst_ids_dev + done, n_tokens_dev + done, row_pieces,
+                           pieces, g.num_blocks);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return set_hip_error(e);
+    }
+    return GLM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+// Internal declarations shared by the host side and the kernels of libglm.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <vector>
+
+#include "glm.h"
+
+namespace glm {
+
+constexpr int kBlockSize = 16;        // tokens per KV block = one MFMA M tile
+constexpr int kXcds = 8;              // L2 domains of the chip; workgroup i runs on XCD i % 8
+constexpr int kRowsPerWave = 16;      // query rows (MFMA N) one wave owns
+constexpr int kBigWaves = 4;          // waves of a workgroup that shares staged K/V over 64 rows
+constexpr int kMaxImplicitSplits = 32;
+
+enum PlanKind : int32_t { kDecode = 0, kPrefill = 1 };
+
+// merge_kind values of a request in a decode plan
+enum MergeKind : int32_t { kMergeList = 0, kMergeDirect = 1, kMergeZero = 2 };
+
+struct DevicePlan {                   // pointers into the plan's single device allocation
+    const glm_chunk *chunks[2] = {nullptr, nullptr};   // [0]: 1-wave workgroups, [1]: 4-wave workgroups
+    int32_t n_chunks[2] = {0, 0};     // multiples of kXcds (padded with n_mem == 0 entries)
+    const int32_t *members = nullptr;
+    const int32_t *merge_off = nullptr;   // [B+1]
+    const int32_t *merge_slots = nullptr; // member-slot indices, request by request
+    const int32_t *merge_kind = nullptr;  // [B]
+};
+
+int set_hip_error(hipError_t e);      // records e for glm_last_hip_error, returns GLM_ERR_HIP
+int check_geom(const glm_geom &g);
+bool validate_enabled();
+
+}  // namespace glm
+
+struct glm_plan {
+    glm_geom g{};
+    int32_t B = 0, max_blocks = 0;
+    int32_t kind = glm::kDecode;
+    std::vector<glm_chunk> chunks[2];
+    std::vector<int32_t> members, merge_off, merge_slots, merge_kind;
+    int32_t n_slots = 0;              // member slots; a slot holds Hq partial rows
+    int32_t n_shared_segments = 0;
+    int64_t shared_blocks = 0;
+    void *dev = nullptr;              // device allocation, nullptr for host-only plans
+    int device = -1;
+    glm::DevicePlan d;
+    std::vector<char> staging;        // host image of the device allocation (kept for the async upload)
+};

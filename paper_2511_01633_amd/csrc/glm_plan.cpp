@@ -1,0 +1,394 @@
+// Host-side plan builder: prefix tree of shared block runs -> work list + merge lists.
+//
+// Sharing structure (paper Sec. 5.1-5.2): prompts are an agent-template prefix, then graph
+// context / notebook chunks reused by the branches of a query, then a private suffix, so the
+// block tables of a batch form a prefix tree.  A run of logical blocks that one set of
+// requests references through identical physical ids is streamed from HBM once and applied
+// to the query rows of every member.
+#include <algorithm>
+#include <climits>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "glm_internal.h"
+
+namespace glm {
+
+namespace {
+
+struct Segment {
+    std::vector<int32_t> members;
+    int32_t b0, b1;
+    bool open;   // runs to the end of its (single) member's sequence
+};
+
+inline int32_t ceil_div(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
+
+// Splits `members` (all reference identical blocks before `start`) into segments.
+void build_segments(const int32_t *tables, int32_t max_blocks, const std::vector<int32_t> &nblk,
+                    std::vector<int32_t> members, int32_t start, std::vector<Segment> &out) {
+    struct Frame { std::vector<int32_t> members; int32_t start; };
+    std::vector<Frame> stack;
+    stack.push_back({std::move(members), start});
+    while (!stack.empty()) {
+        Frame f = std::move(stack.back());
+        stack.pop_back();
+        std::vector<int32_t> &m = f.members;
+        int32_t i = f.start;
+        while (true) {
+            if (m.size() == 1) {
+                if (nblk[m[0]] > f.start) out.push_back({m, f.start, nblk[m[0]], true});
+                break;
+            }
+            size_t active = 0;
+            for (int32_t r : m) active += nblk[r] > i;
+            if (active == 0) {
+                if (i > f.start) out.push_back({m, f.start, i, false});
+                break;
+            }
+            if (active < m.size()) {
+                if (i > f.start) out.push_back({m, f.start, i, false});
+                std::vector<int32_t> rest;
+                for (int32_t r : m) if (nblk[r] > i) rest.push_back(r);
+                stack.push_back({std::move(rest), i});
+                break;
+            }
+            const int32_t id0 = tables[(int64_t)m[0] * max_blocks + i];
+            bool same = true;
+            for (int32_t r : m) same &= tables[(int64_t)r * max_blocks + i] == id0;
+            if (same) { ++i; continue; }
+            if (i > f.start) out.push_back({m, f.start, i, false});
+            // partition by physical id at logical block i, keeping request order inside a part
+            std::vector<std::pair<int32_t, int32_t>> keyed;
+            keyed.reserve(m.size());
+            for (int32_t r : m) keyed.push_back({tables[(int64_t)r * max_blocks + i], r});
+            std::stable_sort(keyed.begin(), keyed.end(),
+                             [](const std::pair<int32_t, int32_t> &a, const std::pair<int32_t, int32_t> &b) { return a.first < b.first; });
+            size_t p = 0;
+            std::vector<Frame> parts;
+            while (p < keyed.size()) {
+                size_t e = p;
+                std::vector<int32_t> part;
+                while (e < keyed.size() && keyed[e].first == keyed[p].first) part.push_back(keyed[e++].second);
+                parts.push_back({std::move(part), i});
+                p = e;
+            }
+            for (auto it = parts.rbegin(); it != parts.rend(); ++it) stack.push_back(std::move(*it));
+            break;
+        }
+    }
+}
+
+struct Work {
+    glm_chunk c;
+    int64_t cost;
+};
+
+int env_int(const char *name, int dflt) {
+    const char *s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    return std::atoi(s);
+}
+
+// Deals the work of one launch onto the 8 XCDs: neighbours in `w` (which share K/V) stay on
+// one XCD, each XCD gets about the same cost, and inside an XCD the costly items go first.
+std::vector<glm_chunk> deal_to_xcds(std::vector<Work> &w) {
+    std::vector<glm_chunk> out;
+    if (w.empty()) return out;
+    int64_t total = 0;
+    for (auto &x : w) total += x.cost;
+    std::vector<std::vector<Work>> per(kXcds);
+    int64_t acc = 0;
+    size_t xcd = 0;
+    for (auto &x : w) {
+        // boundary k sits at total*k/8; an item goes to the XCD its midpoint falls in
+        const int64_t mid = acc + x.cost / 2;
+        size_t want = (size_t)std::min<int64_t>(kXcds - 1, total > 0 ? mid * kXcds / total : 0);
+        if (want > xcd) xcd = want;
+        per[xcd].push_back(x);
+        acc += x.cost;
+    }
+    size_t longest = 0;
+    for (auto &v : per) {
+        std::stable_sort(v.begin(), v.end(), [](const Work &a, const Work &b) { return a.cost > b.cost; });
+        longest = std::max(longest, v.size());
+    }
+    glm_chunk pad{};
+    pad.n_mem = 0;
+    pad.slot0 = -1;
+    out.resize(longest * kXcds, pad);
+    for (size_t x = 0; x < (size_t)kXcds; ++x)
+        for (size_t k = 0; k < per[x].size(); ++k) out[k * kXcds + x] = per[x][k].c;
+    return out;
+}
+
+int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
+    const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
+    std::vector<int32_t> nblk(B);
+    for (int32_t r = 0; r < B; ++r) {
+        if (seq_lens[r] < 0 || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks) return GLM_ERR_RANGE;
+        nblk[r] = ceil_div(seq_lens[r], kBlockSize);
+    }
+    std::vector<int32_t> all(B);
+    std::iota(all.begin(), all.end(), 0);
+    std::vector<Segment> segs;
+    if (B > 0) build_segments(tables, p.max_blocks, nblk, all, 0, segs);
+
+    // chunk length: aim at a few workgroups per SIMD over the whole launch
+    int64_t units = 0;
+    for (auto &s : segs) {
+        const int64_t rows = (int64_t)s.members.size() * G;
+        const int waves = rows > kRowsPerWave ? kBigWaves : 1;
+        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kRowsPerWave * waves);
+    }
+    const int target = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 12);
+    int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
+    cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
+    cb = (cb + 1) & ~1;   // whole 32-token tiles
+    if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb = std::max(1, forced);
+
+    std::vector<std::vector<int32_t>> per_req(B);
+    std::vector<Work> work[2];
+    p.members.clear();
+    p.n_slots = 0;
+    p.n_shared_segments = 0;
+    p.shared_blocks = 0;
+    std::vector<int32_t> n_chunks_of(B, 0);
+    for (auto &s : segs) {
+        const int32_t len = s.b1 - s.b0;
+        const int32_t nc = ceil_div(len, cb);
+        for (int32_t r : s.members) n_chunks_of[r] += nc;
+    }
+    for (auto &s : segs) {
+        const int32_t nm = (int32_t)s.members.size();
+        if (nm >= 2) { ++p.n_shared_segments; p.shared_blocks += s.b1 - s.b0; }
+        const int32_t mem_off = (int32_t)p.members.size();
+        p.members.insert(p.members.end(), s.members.begin(), s.members.end());
+        const int64_t rows = (int64_t)nm * G;
+        const int waves = rows > kRowsPerWave ? kBigWaves : 1;
+        const int32_t tile_rows = kRowsPerWave * waves;
+        const int32_t len = s.b1 - s.b0;
+        const int32_t nc = ceil_div(len, cb);
+        // spread the blocks evenly over the nc chunks, in whole tiles of 2 blocks
+        int32_t per_chunk = ceil_div(len, nc);
+        per_chunk = (per_chunk + 1) & ~1;
+        for (int32_t k = 0; k < nc; ++k) {
+            const int32_t c0 = s.b0 + k * per_chunk;
+            if (c0 >= s.b1) break;
+            const bool last = (k == nc - 1) || (c0 + per_chunk >= s.b1);
+            const int32_t c1 = last ? s.b1 : c0 + per_chunk;
+            const bool direct = (nm == 1 && n_chunks_of[s.members[0]] == 1 && last && k == 0);
+            int32_t slot0 = -1;
+            if (!direct) {
+                slot0 = p.n_slots;
+                p.n_slots += nm;
+                for (int32_t mi = 0; mi < nm; ++mi) per_req[s.members[mi]].push_back(slot0 + mi);
+            }
+            for (int32_t row0 = 0; row0 < rows; row0 += tile_rows) {
+                glm_chunk c{};
+                c.rep = s.members[0];
+                c.b0 = c0;
+                c.b1 = (s.open && last) ? INT32_MAX : c1;
+                c.mem_off = mem_off;
+                c.n_mem = nm;
+                c.row0 = row0;
+                c.slot0 = slot0;
+                c.waves = waves;
+                const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), kRowsPerWave);
+                work[waves == 1 ? 0 : 1].push_back({c, (int64_t)(c1 - c0) * (4 + tiles_here)});
+            }
+            if (last) break;
+        }
+    }
+    p.merge_off.assign(B + 1, 0);
+    p.merge_kind.assign(B, kMergeList);
+    p.merge_slots.clear();
+    for (int32_t r = 0; r < B; ++r) {
+        p.merge_off[r] = (int32_t)p.merge_slots.size();
+        if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
+        else if (per_req[r].empty()) p.merge_kind[r] = kMergeDirect;
+        p.merge_slots.insert(p.merge_slots.end(), per_req[r].begin(), per_req[r].end());
+    }
+    p.merge_off[B] = (int32_t)p.merge_slots.size();
+    for (int k = 0; k < 2; ++k) p.chunks[k] = deal_to_xcds(work[k]);
+    return GLM_OK;
+}
+
+int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
+    const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
+    const int32_t tile_rows = kRowsPerWave * kBigWaves;
+    std::vector<Work> work;
+    for (int32_t r = 0; r < B; ++r) {
+        if (q_lens[r] < 0 || seq_lens[r] < q_lens[r] || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks)
+            return GLM_ERR_RANGE;
+        const int64_t rows = (int64_t)q_lens[r] * G;
+        const int64_t ctx = seq_lens[r] - q_lens[r];
+        for (int64_t row0 = 0; row0 < rows; row0 += tile_rows) {
+            glm_chunk c{};
+            c.rep = r;
+            c.b0 = 0;
+            c.b1 = INT32_MAX;
+            c.mem_off = 0;
+            c.n_mem = q_lens[r];
+            c.row0 = (int32_t)row0;
+            c.slot0 = -1;
+            c.waves = kBigWaves;
+            const int64_t last_pos = std::min<int64_t>(rows, row0 + tile_rows) - 1;
+            const int64_t visible = ctx + last_pos / G + 1;
+            work.push_back({c, ceil_div(visible, kBlockSize)});
+        }
+    }
+    p.chunks[0].clear();
+    p.chunks[1] = deal_to_xcds(work);
+    p.members.clear();
+    p.merge_off.assign(B + 1, 0);
+    p.merge_slots.clear();
+    p.merge_kind.assign(B, kMergeDirect);
+    p.n_slots = 0;
+    return GLM_OK;
+}
+
+template <class T>
+size_t append(std::vector<char> &buf, const std::vector<T> &v) {
+    size_t off = (buf.size() + 255) & ~(size_t)255;
+    buf.resize(off + std::max<size_t>(v.size() * sizeof(T), sizeof(T)), 0);
+    if (!v.empty()) std::memcpy(buf.data() + off, v.data(), v.size() * sizeof(T));
+    return off;
+}
+
+}  // namespace
+
+int check_geom(const glm_geom &g) {
+    if (g.num_blocks <= 0 || g.num_kv_heads <= 0 || g.num_q_heads <= 0) return GLM_ERR_GEOM;
+    if (g.block_size != kBlockSize) return GLM_ERR_GEOM;
+    if (g.head_dim != 64 && g.head_dim != 128) return GLM_ERR_GEOM;
+    if (g.num_q_heads % g.num_kv_heads != 0) return GLM_ERR_GEOM;
+    return GLM_OK;
+}
+
+}  // namespace glm
+
+using namespace glm;
+
+static glm_plan *plan_build(glm_geom g, const int32_t *tables, int32_t max_blocks, const int32_t *seq_lens,
+                            const int32_t *q_lens, int32_t B, int *status) {
+    int st = GLM_OK;
+    glm_plan *p = nullptr;
+    if (!tables || !seq_lens) st = GLM_ERR_NULL;
+    else if ((st = check_geom(g)) == GLM_OK && (B < 0 || max_blocks <= 0)) st = GLM_ERR_GEOM;
+    if (st == GLM_OK) {
+        try {
+            p = new glm_plan();
+            p->g = g;
+            p->B = B;
+            p->max_blocks = max_blocks;
+            p->kind = q_lens ? kPrefill : kDecode;
+            st = q_lens ? build_prefill(*p, seq_lens, q_lens) : build_decode(*p, tables, seq_lens);
+        } catch (const std::bad_alloc &) {
+            st = GLM_ERR_ALLOC;
+        } catch (...) {
+            st = GLM_ERR_ALLOC;
+        }
+        if (st != GLM_OK) { delete p; p = nullptr; }
+    }
+    if (status) *status = st;
+    return p;
+}
+
+extern "C" {
+
+glm_plan *glm_plan_create_host(glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
+                               const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B, int *status) {
+    return plan_build(g, block_tables_host, max_blocks, seq_lens_host, q_lens_host, B, status);
+}
+
+glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
+                          const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B, void *hip_stream,
+                          int *status) {
+    int st = GLM_OK;
+    glm_plan *p = plan_build(g, block_tables_host, max_blocks, seq_lens_host, q_lens_host, B, &st);
+    if (p) {
+        try {
+            std::vector<char> &buf = p->staging;
+            const size_t o_c0 = append(buf, p->chunks[0]);
+            const size_t o_c1 = append(buf, p->chunks[1]);
+            const size_t o_mem = append(buf, p->members);
+            const size_t o_off = append(buf, p->merge_off);
+            const size_t o_slots = append(buf, p->merge_slots);
+            const size_t o_kind = append(buf, p->merge_kind);
+            hipError_t e = hipGetDevice(&p->device);
+            if (e == hipSuccess) e = hipMalloc(&p->dev, buf.size());
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(p->dev, buf.data(), buf.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
+            if (e != hipSuccess) {
+                st = set_hip_error(e);
+                if (p->dev) (void)hipFree(p->dev);
+                delete p;
+                p = nullptr;
+            } else {
+                char *d = (char *)p->dev;
+                p->d.chunks[0] = (const glm_chunk *)(d + o_c0);
+                p->d.chunks[1] = (const glm_chunk *)(d + o_c1);
+                p->d.n_chunks[0] = (int32_t)p->chunks[0].size();
+                p->d.n_chunks[1] = (int32_t)p->chunks[1].size();
+                p->d.members = (const int32_t *)(d + o_mem);
+                p->d.merge_off = (const int32_t *)(d + o_off);
+                p->d.merge_slots = (const int32_t *)(d + o_slots);
+                p->d.merge_kind = (const int32_t *)(d + o_kind);
+            }
+        } catch (...) {
+            st = GLM_ERR_ALLOC;
+            delete p;
+            p = nullptr;
+        }
+    }
+    if (status) *status = st;
+    return p;
+}
+
+void glm_plan_destroy(glm_plan *plan) {
+    if (!plan) return;
+    if (plan->dev) {
+        // the upload may still be in flight on the creating stream
+        (void)hipDeviceSynchronize();
+        (void)hipFree(plan->dev);
+    }
+    delete plan;
+}
+
+size_t glm_plan_workspace_bytes(const glm_plan *plan) {
+    if (!plan) return 0;
+    const size_t rows = (size_t)plan->n_slots * plan->g.num_q_heads;
+    return std::max<size_t>(256, rows * (size_t)(plan->g.head_dim + 2) * sizeof(float));
+}
+
+int32_t glm_plan_num_chunks(const glm_plan *plan) {
+    return plan ? (int32_t)(plan->chunks[0].size() + plan->chunks[1].size()) : 0;
+}
+
+int32_t glm_plan_get_chunks(const glm_plan *plan, glm_chunk *out, int32_t capacity) {
+    if (!plan || !out) return 0;
+    int32_t n = 0;
+    for (int k = 0; k < 2; ++k)
+        for (const glm_chunk &c : plan->chunks[k]) {
+            if (n >= capacity) return n;
+            out[n++] = c;
+        }
+    return n;
+}
+
+int32_t glm_plan_num_members(const glm_plan *plan) { return plan ? (int32_t)plan->members.size() : 0; }
+
+int32_t glm_plan_get_members(const glm_plan *plan, int32_t *out, int32_t capacity) {
+    if (!plan || !out) return 0;
+    const int32_t n = std::min<int32_t>(capacity, (int32_t)plan->members.size());
+    std::memcpy(out, plan->members.data(), (size_t)n * sizeof(int32_t));
+    return n;
+}
+
+int32_t glm_plan_num_shared_segments(const glm_plan *plan) { return plan ? plan->n_shared_segments : 0; }
+int64_t glm_plan_shared_blocks(const glm_plan *plan) { return plan ? plan->shared_blocks : 0; }
+
+}  // extern "C"

@@ -1,0 +1,313 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Attention: max abs error <= 4e-3 (bf16 inputs, fp32 accumulate, fp32 output);
+copies: bit exact."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _gu():
+    import gpu_util
+    return gpu_util
+
+
+def _oracle(w):
+    return oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, cu_q_lens=w.cu_q_lens)
+
+
+def _check(got, ref, what):
+    gu = _gu()
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err = np.abs(got - ref).max() if ref.size else 0.0
+    print("%s: max abs err %.3e" % (what, err), flush=True)
+    assert err <= gu.TOL, "%s: max abs err %.3e > %.1e" % (what, err, gu.TOL)
+    return err
+
+
+# ------------------------------------------------------------------ copies (bit exact)
+
+@pytest.mark.parametrize("hkv,d", [(8, 128), (4, 64), (1, 64)])
+def test_gather_bit_exact(hkv, d):
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    rng = np.random.default_rng(5)
+    geom = W.Geometry(96, 16, hkv, hkv, d)
+    src = rng.integers(0, 65536, size=(96, 2, hkv, 16, d), dtype=np.uint16)
+    ids = rng.permutation(96)[:37].astype(np.int32)
+    # pack to staging
+    staged_ref = np.full((40, 2, hkv, 16, d), 0x1111, np.uint16)
+    oracle.gather(geom, src, ids, staged_ref, None)
+    d_src, d_staged = gu.dev(src), gu.dev(np.full_like(staged_ref, 0x1111))
+    glm.glm_kv_gather(geom, d_src, gu.dev(ids), d_staged, None, ids.size)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(d_staged), staged_ref)
+    # re-admit into other slots of a second pool
+    slots = rng.permutation(96)[:37].astype(np.int32)
+    back_ref = np.full_like(src, 0x2222)
+    oracle.gather(geom, staged_ref, None, back_ref, slots, n=37)
+    d_back = gu.dev(np.full_like(src, 0x2222))
+    glm.glm_kv_gather(geom, d_staged, None, d_back, gu.dev(slots), 37)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(d_back), back_ref)
+    # both lists
+    both_ref = np.full_like(src, 0x3333)
+    oracle.gather(geom, src, ids, both_ref, slots)
+    d_both = gu.dev(np.full_like(src, 0x3333))
+    glm.glm_kv_gather(geom, d_src, gu.dev(ids), d_both, gu.dev(slots), 37)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(d_both), both_ref)
+    # n == 0 is a no-op
+    assert glm.glm_kv_gather(geom, d_src, None, d_both, None, 0) == 0
+
+
+@pytest.mark.parametrize("hkv,d", [(8, 128), (2, 64)])
+def test_fork_copy_bit_exact(hkv, d):
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    rng = np.random.default_rng(6)
+    geom = W.Geometry(64, 16, hkv, hkv, d)
+    pool = rng.integers(0, 65536, size=(64, 2, hkv, 16, d), dtype=np.uint16)
+    perm = rng.permutation(64)
+    src = np.concatenate([perm[:20], perm[:4]]).astype(np.int32)       # some sources feed two destinations
+    dst = perm[20:44].astype(np.int32)
+    ntok = np.concatenate([np.arange(0, 17), rng.integers(0, 17, size=7)]).astype(np.int32)
+    ref = pool.copy()
+    oracle.fork_copy(geom, ref, src, dst, ntok)
+    d_pool = gu.dev(pool)
+    glm.glm_kv_fork_copy(geom, d_pool, gu.dev(src), gu.dev(dst), gu.dev(ntok), src.size)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(d_pool), ref)
+    assert glm.glm_kv_fork_copy(geom, d_pool, gu.dev(src), gu.dev(dst), gu.dev(ntok), 0) == 0
+
+
+# ------------------------------------------------------------------ decode
+
+def _decode_both_ways(w, what):
+    gu = _gu()
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    got_np = dw.decode(plan=None)
+    _check(got_np, ref, what + " (no plan)")
+    plan = dw.make_plan()
+    got_p = dw.decode(plan=plan)
+    _check(got_p, ref, what + " (plan)")
+    assert np.abs(got_p - got_np).max() <= 1e-5, "plan changes the result"
+    again = dw.decode(plan=plan)
+    np.testing.assert_array_equal(again, got_p)          # no atomics, fixed merge order: reruns are bit identical
+    return dw, plan, got_p, ref
+
+
+def test_decode_tiny_config():
+    w = W.tiny_decode()
+    _decode_both_ways(w, "tiny_decode")
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 4, 64), (8, 2, 128), (8, 1, 64), (32, 8, 128), (6, 2, 128), (40, 2, 64)])
+def test_decode_small_shapes(hq, hkv, d):
+    # two prefix groups of different depth plus two branches with no shared prefix; lengths cover
+    # one-token tails, exact tile multiples, odd block counts and a ragged last block
+    sfx = [0, 1, 15, 16, 31, 32, 47, 100, 257, 5, 33, 64]
+    w = W.custom_decode(1000 + hq * 10 + d, prefix_groups=[[0, 1, 2, 3, 4], [5, 6, 7, 8, 9]], prefix_tokens=[48, 272],
+                        suffix_tokens=sfx, num_q_heads=hq, num_kv_heads=hkv, head_dim=d, occupancy=0.6)
+    _decode_both_ways(w, "decode %d/%d d%d" % (hq, hkv, d))
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 4, 16, 17])
+def test_decode_very_short_sequences(L):
+    w = W.custom_decode(2000 + L, prefix_groups=[], prefix_tokens=[], suffix_tokens=[L - 1] * 3 + [max(L - 2, 0)],
+                        num_q_heads=8, num_kv_heads=2, head_dim=128)
+    dw, plan, got, ref = _decode_both_ways(w, "decode L=%d" % L)
+    if L == 1:
+        np.testing.assert_array_equal(got[:3], ref[:3])   # one key: the output is v0 exactly
+
+
+def test_decode_empty_request_and_batch_of_one():
+    w = W.custom_decode(2100, prefix_groups=[[0, 1]], prefix_tokens=[32], suffix_tokens=[3, 9, 20], num_q_heads=8,
+                        num_kv_heads=2, head_dim=64)
+    w.seq_lens[2] = 0
+    dw, plan, got, ref = _decode_both_ways(w, "decode with an empty request")
+    assert (got[2] == 0).all()
+    w1 = W.custom_decode(2101, prefix_groups=[], prefix_tokens=[], suffix_tokens=[700], num_q_heads=32, num_kv_heads=8,
+                         head_dim=128)
+    _decode_both_ways(w1, "decode B=1")
+
+
+def test_decode_shared_equals_duplicated_prefix_and_permutation():
+    gu = _gu()
+    w = W.custom_decode(2200, prefix_groups=[[0, 1, 2, 3, 4, 5]], prefix_tokens=[160], suffix_tokens=[4, 40, 17, 0, 90, 33],
+                        num_q_heads=16, num_kv_heads=4, head_dim=128, occupancy=0.3)
+    dw, plan, got, ref = _decode_both_ways(w, "shared prefix")
+    # duplicate the prefix physically per branch: same numbers expected (sharing is exact)
+    npre = 160 // 16
+    used = set(int(x) for x in w.live_block_ids())
+    free = [b for b in range(w.geom.num_blocks) if b not in used]
+    pool = w.pool.copy(); tables = w.block_tables.copy()
+    for r in range(1, w.B):
+        for i in range(npre):
+            nb = free.pop(); pool[nb] = w.pool[tables[r, i]]; tables[r, i] = nb
+    w2 = W.Workload("dup", w.geom, pool, w.q, tables, w.seq_lens, w.scale)
+    dw2, plan2, got2, ref2 = _decode_both_ways(w2, "duplicated prefix")
+    np.testing.assert_array_equal(ref, ref2)
+    assert np.abs(got - got2).max() <= 1e-5
+    assert plan.num_shared_segments == 1 and plan2.num_shared_segments == 0
+    # permute physical ids
+    perm = np.random.default_rng(1).permutation(w.geom.num_blocks)
+    pool3 = np.empty_like(w.pool); pool3[perm] = w.pool
+    tables3 = np.where(w.block_tables >= 0, perm[np.clip(w.block_tables, 0, None)], -1).astype(np.int32)
+    w3 = W.Workload("perm", w.geom, pool3, w.q, tables3, w.seq_lens, w.scale)
+    dw3 = gu.DeviceWorkload(w3)
+    got3 = dw3.decode(plan=dw3.make_plan())
+    np.testing.assert_array_equal(got3, got)              # same chunks, same order: identical bits
+
+
+def test_decode_plan_survives_growth_of_private_tails():
+    gu = _gu()
+    w = W.custom_decode(2300, prefix_groups=[[0, 1, 2]], prefix_tokens=[64], suffix_tokens=[5, 18, 40, 7],
+                        num_q_heads=8, num_kv_heads=2, head_dim=128, extra_table_cols=3, occupancy=0.4)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    # every request decodes 20 more tokens: tails get new blocks appended, the shared topology is unchanged
+    used = set(int(x) for x in w.live_block_ids())
+    free = [b for b in range(w.geom.num_blocks) if b not in used]
+    rng = np.random.default_rng(3)
+    for r in range(w.B):
+        old_nb = -(-int(w.seq_lens[r]) // 16)
+        w.seq_lens[r] += 20
+        for i in range(old_nb, -(-int(w.seq_lens[r]) // 16)):
+            nb = free.pop(); w.block_tables[r, i] = nb
+            w.pool[nb] = W.f32_to_bf16_bits(rng.standard_normal(w.pool.shape[1:], dtype=np.float32))
+        # rows of the old last block that were unfilled are now visible: give them real data
+    live = w.live_block_ids()
+    w.pool[live] = np.where(w.pool[live] == W.gen.SENTINEL_BITS,
+                            W.f32_to_bf16_bits(rng.standard_normal(w.pool[live].shape, dtype=np.float32)), w.pool[live])
+    dw2 = gu.DeviceWorkload(w)
+    got = dw2.decode(plan=plan)
+    _check(got, _oracle(w), "stale-but-valid plan after growth")
+
+
+# ------------------------------------------------------------------ prefill on a cached prefix
+
+def _prefill_both_ways(w, what):
+    gu = _gu()
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    got = dw.prefill(plan=None)
+    _check(got, ref, what + " (no plan)")
+    plan = dw.make_plan()
+    got_p = dw.prefill(plan=plan)
+    _check(got_p, ref, what + " (plan)")
+    np.testing.assert_array_equal(got_p, got)
+    return got, ref
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 64), (32, 8, 128), (12, 4, 64)])
+def test_prefill_small_shapes(hq, hkv, d):
+    w = W.custom_prefill(3000 + hq + d, prefix_groups=[[0, 1, 2], [3, 4]], prefix_tokens=[80, 16],
+                         q_lens=[1, 17, 64, 33, 100, 5, 0, 48], num_q_heads=hq, num_kv_heads=hkv, head_dim=d)
+    _prefill_both_ways(w, "prefill %d/%d d%d" % (hq, hkv, d))
+
+
+def test_prefill_without_any_cached_prefix_and_row_vs_decode():
+    w = W.custom_prefill(3100, prefix_groups=[], prefix_tokens=[], q_lens=[4, 1, 37], num_q_heads=8, num_kv_heads=2,
+                         head_dim=128)
+    got, ref = _prefill_both_ways(w, "prefill ctx=0")
+    # first new token of a request with nothing cached sees one key: exactly v0
+    np.testing.assert_array_equal(got[0], ref[0])
+
+
+# ------------------------------------------------------------------ the configurations at full size
+
+def _sample_rows(w, n, seed):
+    rng = np.random.default_rng(seed)
+    req = rng.integers(0, w.B, size=n).astype(np.int32)
+    head = rng.integers(0, w.geom.num_q_heads, size=n).astype(np.int32)
+    head[0], head[1] = 0, w.geom.num_q_heads - 1
+    if w.q_lens is None:
+        return req, None, head
+    idx = np.array([rng.integers(0, int(w.q_lens[r])) for r in req], np.int32)
+    idx[0], idx[1] = 0, int(w.q_lens[req[1]]) - 1
+    return req, idx, head
+
+
+def test_llama8b_decode_full():
+    w = W.llama8b_decode()
+    dw, plan, got, ref = _decode_both_ways(w, "llama8b_decode")
+    assert plan.num_shared_segments == 4 and plan.shared_blocks == 4 * 128
+
+
+def test_prefill_on_prefix_full_sampled():
+    gu = _gu()
+    w = W.prefill_on_prefix()
+    dw = gu.DeviceWorkload(w)
+    got = dw.prefill(plan=dw.make_plan())
+    assert np.isfinite(got).all()
+    req, idx, head = _sample_rows(w, 192, 11)
+    ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head, sel_i=idx,
+                                cu_q_lens=w.cu_q_lens)
+    rows = w.cu_q_lens[req] + idx
+    _check(got[rows, head], ref, "prefill_on_prefix (192 sampled rows)")
+    got_np = dw.prefill(plan=None)
+    np.testing.assert_array_equal(got_np, got)
+
+
+def test_tree_decode_70b_full_sampled():
+    gu = _gu()
+    w = W.tree_decode_70b()
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    assert plan.num_shared_segments == 9
+    got = dw.decode(plan=plan)
+    assert np.isfinite(got).all()
+    req, _, head = _sample_rows(w, 256, 12)
+    ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head)
+    _check(got[req, head], ref, "tree_decode_70b (256 sampled rows)")
+    got_np = dw.decode(plan=None)
+    assert np.abs(got_np - got).max() <= 1e-5
+
+
+def test_eviction_churn_step_full_sampled():
+    """One churn step: fork copy-on-write of partly filled last blocks, eviction of 2 % of the live
+    blocks to a staging buffer and re-admission into other free slots, then decode on the new tables."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.eviction_churn()
+    step = W.churn_step(w, 0)
+    dw = gu.DeviceWorkload(w)
+    # oracle side: same operations on the host copy
+    pool_ref = w.pool.copy()
+    oracle.fork_copy(w.geom, pool_ref, step.fork_src, step.fork_dst, step.fork_ntok)
+    n_re = step.evict_ids.size
+    staging_ref = np.zeros((n_re,) + w.pool.shape[1:], np.uint16)
+    oracle.gather(w.geom, pool_ref, step.evict_ids, staging_ref, None)
+    pool_ref[step.evict_ids] = W.gen.SENTINEL_BITS           # evicted slots are dead until something else lands there
+    oracle.gather(w.geom, staging_ref, None, pool_ref, step.readmit_ids, n=n_re)
+    # GPU side
+    glm.glm_kv_fork_copy(w.geom, dw.pool, gu.dev(step.fork_src), gu.dev(step.fork_dst), gu.dev(step.fork_ntok),
+                         step.fork_src.size)
+    staging = torch.zeros((n_re,) + w.pool.shape[1:], dtype=torch.int16, device="cuda")
+    glm.glm_kv_gather(w.geom, dw.pool, gu.dev(step.evict_ids), staging, None, n_re)
+    dw.pool[torch.from_numpy(step.evict_ids.astype(np.int64)).cuda()] = np.int16(W.gen.SENTINEL_BITS)
+    glm.glm_kv_gather(w.geom, staging, None, dw.pool, gu.dev(step.readmit_ids), n_re)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(staging), staging_ref)
+    np.testing.assert_array_equal(gu.host_u16(dw.pool), pool_ref)
+    # decode on the remapped tables
+    w2 = W.Workload("churned", w.geom, pool_ref, w.q, step.block_tables, w.seq_lens, w.scale)
+    dw.tables = gu.dev(step.block_tables)
+    dw.w = w2
+    plan = dw.make_plan()
+    got = dw.decode(plan=plan)
+    assert np.isfinite(got).all()
+    req, _, head = _sample_rows(w2, 256, 13)
+    longest = int(np.argmax(w.seq_lens)); shortest = int(np.argmin(w.seq_lens))
+    req[2], req[3] = longest, shortest
+    ref = oracle.attention_rows(w2.geom, w2.pool, w2.q, w2.block_tables, w2.seq_lens, w2.scale, req, head)
+    _check(got[req, head], ref, "eviction_churn after one step (256 sampled rows)")
+    got_np = dw.decode(plan=None)
+    assert np.abs(got_np - got).max() <= 1e-5

@@ -1,0 +1,151 @@
+"""Host-side logic of the library that needs no GPU: exported symbols, status codes of the
+argument checks (they return before any HIP call), and the plan builder."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+glm = pytest.importorskip("paper_2511_01633_amd")
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "glm.h")).read()
+    declared = set(re.findall(r"GLM_API[^;(]*?\b(glm_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(glm.EXPORTS), declared ^ set(glm.EXPORTS)
+    lib = ctypes.CDLL(glm.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert glm.glm_version() >= 100
+    assert glm.glm_status_string(0) == "ok" and "workspace" in glm.glm_status_string(glm.GLM_ERR_WORKSPACE)
+
+
+GEOM = W.Geometry(64, 16, 2, 8, 128)
+FAKE = 0x1000   # a non-NULL, 16-byte aligned address that is never dereferenced: every call below fails its checks first
+
+
+def _decode(g=GEOM, pool=FAKE, q=FAKE, out=FAKE, tables=FAKE, max_blocks=4, lens=FAKE, B=2, ws=FAKE, ws_bytes=1 << 20,
+            plan=None):
+    return glm.glm_attn_decode(g, pool, q, out, tables, max_blocks, lens, B, 0.1, plan, ws, ws_bytes, hip_stream=0,
+                               check=False)
+
+
+def test_decode_argument_checks():
+    assert _decode(B=0) == glm.GLM_OK
+    assert _decode(pool=None) == glm.GLM_ERR_NULL
+    assert _decode(lens=None) == glm.GLM_ERR_NULL
+    assert _decode(g=W.Geometry(64, 16, 3, 8, 128)) == glm.GLM_ERR_GEOM          # Hq % Hkv
+    assert _decode(g=W.Geometry(64, 32, 2, 8, 128)) == glm.GLM_ERR_GEOM          # block size
+    assert _decode(g=W.Geometry(64, 16, 2, 8, 96)) == glm.GLM_ERR_GEOM           # head_dim
+    assert _decode(g=W.Geometry(0, 16, 2, 8, 128)) == glm.GLM_ERR_GEOM
+    assert _decode(B=-1) == glm.GLM_ERR_GEOM
+    assert _decode(max_blocks=0) == glm.GLM_ERR_GEOM
+    assert _decode(q=FAKE + 8) == glm.GLM_ERR_ALIGN
+    assert _decode(ws=None, ws_bytes=0) == glm.GLM_ERR_WORKSPACE
+    assert _decode(ws_bytes=100) == glm.GLM_ERR_WORKSPACE
+    with pytest.raises(glm.GlmError):
+        glm.glm_attn_decode(GEOM, None, FAKE, FAKE, FAKE, 4, FAKE, 2, 0.1, None, FAKE, 1 << 20, hip_stream=0)
+
+
+def test_prefill_and_copy_argument_checks():
+    def pf(**kw):
+        a = dict(g=GEOM, pool=FAKE, q=FAKE, out=FAKE, tables=FAKE, mb=4, lens=FAKE, cu=FAKE, B=2, sum_q=8, mq=4)
+        a.update(kw)
+        return glm.glm_attn_prefill_on_prefix(a["g"], a["pool"], a["q"], a["out"], a["tables"], a["mb"], a["lens"],
+                                              a["cu"], a["B"], a["sum_q"], a["mq"], 0.1, None, None, 0, hip_stream=0,
+                                              check=False)
+    assert pf(B=0) == glm.GLM_OK and pf(sum_q=0) == glm.GLM_OK
+    assert pf(cu=None) == glm.GLM_ERR_NULL
+    assert pf(out=FAKE + 4) == glm.GLM_ERR_ALIGN
+    assert pf(sum_q=-1) == glm.GLM_ERR_GEOM
+    assert pf(g=W.Geometry(64, 16, 2, 8, 256)) == glm.GLM_ERR_GEOM
+    assert glm.glm_kv_gather(GEOM, FAKE, None, FAKE, None, 0, hip_stream=0, check=False) == glm.GLM_OK
+    assert glm.glm_kv_gather(GEOM, None, None, FAKE, None, 3, hip_stream=0, check=False) == glm.GLM_ERR_NULL
+    assert glm.glm_kv_gather(GEOM, FAKE, None, FAKE + 2, None, 3, hip_stream=0, check=False) == glm.GLM_ERR_ALIGN
+    assert glm.glm_kv_gather(GEOM, FAKE, None, FAKE, None, -3, hip_stream=0, check=False) == glm.GLM_ERR_GEOM
+    assert glm.glm_kv_fork_copy(GEOM, FAKE, FAKE, FAKE, FAKE, 0, hip_stream=0, check=False) == glm.GLM_OK
+    assert glm.glm_kv_fork_copy(GEOM, FAKE, None, FAKE, FAKE, 2, hip_stream=0, check=False) == glm.GLM_ERR_NULL
+    assert glm.glm_kv_fork_copy(GEOM, FAKE + 1, FAKE, FAKE, FAKE, 2, hip_stream=0, check=False) == glm.GLM_ERR_ALIGN
+
+
+def test_plan_mismatch_and_host_only_plans_are_rejected():
+    w = W.custom_decode(1, prefix_groups=[[0, 1]], prefix_tokens=[32], suffix_tokens=[3, 9], num_q_heads=8,
+                        num_kv_heads=2, head_dim=128)
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    # host-only plan has no device lists
+    assert _decode(g=w.geom, max_blocks=w.max_blocks, B=w.B, plan=plan) == glm.GLM_ERR_PLAN_MISMATCH
+    assert _decode(g=w.geom, max_blocks=w.max_blocks + 1, B=w.B, plan=plan) == glm.GLM_ERR_PLAN_MISMATCH
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, np.array([3, 10 ** 6], np.int32), None, w.B)
+    assert e.value.status == glm.GLM_ERR_RANGE
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_plan_create_host(W.Geometry(8, 16, 2, 7, 128), w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    assert e.value.status == glm.GLM_ERR_GEOM
+
+
+def test_decode_plan_covers_every_block_once_and_finds_the_tree():
+    w = W.tree_decode_70b(root_tokens=256, mids=3, mid_tokens=64, leaves_per_mid=5, suffix_tokens=40, num_q_heads=16,
+                          num_kv_heads=2, head_dim=64)
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    assert plan.num_shared_segments == 4                       # the root and three sub-query prefixes
+    assert plan.shared_blocks == 256 // 16 + 3 * (64 // 16)
+    G = w.geom.group
+    members = plan.members()
+    seen = {}
+    for c in plan.chunks():
+        if c.n_mem == 0:
+            continue
+        tile = 16 * c.waves
+        mem = members[c.mem_off:c.mem_off + c.n_mem]
+        lo_row, hi_row = c.row0, min(c.n_mem * G, c.row0 + tile)
+        for rho in range(lo_row, hi_row):
+            r = int(mem[rho // G]); gh = rho % G
+            nb = -(-int(w.seq_lens[r]) // 16)
+            end = nb if c.b1 == 2 ** 31 - 1 else min(c.b1, nb)
+            for b in range(c.b0, end):
+                assert w.block_tables[r, b] == w.block_tables[c.rep, b]
+                seen[(r, gh, b)] = seen.get((r, gh, b), 0) + 1
+    for r in range(w.B):
+        for gh in range(G):
+            for b in range(-(-int(w.seq_lens[r]) // 16)):
+                assert seen.get((r, gh, b), 0) == 1, (r, gh, b)
+    assert len(seen) == sum(-(-int(L) // 16) for L in w.seq_lens) * G
+
+
+def test_plan_handles_partial_sharing_and_unequal_lengths():
+    # request 1 ends inside the run shared with request 0; request 2 shares only the first block
+    tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)
+    lens = np.array([64, 40, 20, 0], np.int32)
+    g = W.Geometry(16, 16, 1, 4, 64)
+    plan = glm.glm_plan_create_host(g, tables, 4, lens, None, 4)
+    ch = [c for c in plan.chunks() if c.n_mem]
+    mem = plan.members()
+    segs = sorted((tuple(int(x) for x in mem[c.mem_off:c.mem_off + c.n_mem]), c.b0, c.b1) for c in ch)
+    assert ((0, 1, 2), 0, 1) in segs          # block 5 shared by three
+    assert ((0, 1), 1, 3) in segs             # blocks 6,7 shared by two (request 1 sees only 8 tokens of block 7)
+    assert any(s[0] == (0,) and s[1] == 3 for s in segs)
+    assert any(s[0] == (2,) and s[1] == 1 for s in segs)
+    assert plan.num_shared_segments == 2 and plan.shared_blocks == 3
+
+
+def test_prefill_plan_tiles_every_row():
+    q_lens = np.array([5, 0, 70, 16], np.int32)
+    lens = q_lens + np.array([32, 0, 0, 100], np.int32)
+    tables = np.arange(4 * 8, dtype=np.int32).reshape(4, 8)
+    g = W.Geometry(64, 16, 2, 8, 128)
+    plan = glm.glm_plan_create_host(g, tables, 8, lens, q_lens, 4)
+    rows = {}
+    for c in plan.chunks():
+        if c.n_mem == 0:
+            continue
+        assert c.waves == 4 and c.slot0 == -1 and c.n_mem == q_lens[c.rep]
+        for rho in range(c.row0, min(c.n_mem * 4, c.row0 + 64)):
+            rows[(c.rep, rho)] = rows.get((c.rep, rho), 0) + 1
+    assert all(v == 1 for v in rows.values())
+    assert len(rows) == int(q_lens.sum()) * 4
+    assert plan.workspace_bytes <= 256
