@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-prefix paged-KV attention path on one MI355X.
+
+Headline (the one JSON line's `value`): decode attention on the Llama-3-8B-shaped layer
+(64 branches on 4 shared 2048-token prefixes), as HBM GB/s over the algorithmic bytes of a
+step - every distinct cached K/V token once, plus Q and the output - with the inputs resident
+in HBM and the KV pools rotated over many distinct copies so that no step finds its blocks in
+L2 or the Infinity Cache.  A step is one pass of the hot path over the batch: the plan
+(built once, reported separately), the streaming kernels and the split-K merge.
+
+`extra` carries the other rows of the path: prefill on a cached prefix (TFLOP/s on the exact
+causal flop count), the 70B-shaped prefix-tree decode, and an eviction-churn step
+(fork copy-on-write + gather out + gather in + decode).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
+    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn (default all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def _dev(a):
+    import numpy as np
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+def _kv_tokens_by_kind(plan, w):
+    """Distinct cached tokens streamed by the 1-wave and by the 4-wave launch (row tiles of one
+    token chunk re-use the same tokens and count once)."""
+    members = plan.members()
+    tok = {1: 0, 4: 0}
+    for c in plan.chunks():
+        if c.n_mem == 0 or c.row0 != 0:
+            continue
+        lim = max(int(w.seq_lens[r]) for r in members[c.mem_off:c.mem_off + c.n_mem])
+        end = lim if c.b1 == 2 ** 31 - 1 else min(c.b1 * 16, lim)
+        tok[c.waves] += max(0, end - c.b0 * 16)
+    return tok
+
+
+def _time_steps(fn, steps, warmup):
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def _kernel_times(glm, fn, steps):
+    """Average duration per launch of each kernel kind, from events on the launch stream."""
+    import torch
+    glm.glm_profile_reset()
+    glm.glm_profile_enable(True)
+    for i in range(steps):
+        fn(i)
+    torch.cuda.synchronize()
+    glm.glm_profile_enable(False)
+    out = {}
+    for name, kid in glm.KERNEL_IDS.items():
+        ms, n = glm.glm_profile_read(kid)
+        if n:
+            out[name] = {"avg_us": ms * 1e3 / n, "launches_per_step": n / steps}
+    glm.glm_profile_reset()
+    return out
+
+
+def _traffic(kernel, workload):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/), if recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        rec = json.load(open(path))
+        return rec.get("%s/%s" % (kernel, workload), {}).get("bytes_per_launch")
+    except Exception:
+        return None
+
+
+def bench_decode(glm, w, layers, steps, warmup):
+    import torch
+    g = w.geom
+    base = _dev(w.pool)
+    pools = [base] + [base.clone() for _ in range(max(1, layers) - 1)]
+    q, tables, lens = _dev(w.q), _dev(w.block_tables), _dev(w.seq_lens)
+    out = torch.empty((w.B, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    t0 = time.perf_counter()
+    plan = glm.glm_plan_create(g, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        glm.glm_attn_decode(g, pools[i % len(pools)], q, out, tables, w.max_blocks, lens, w.B, w.scale, plan, ws)
+
+    ms = _time_steps(step, steps, warmup)
+    kt = _kernel_times(glm, step, min(steps, 64))
+    kv_bytes = w.unique_kv_bytes()
+    io_bytes = w.q.nbytes + out.numel() * 4
+    tok = _kv_tokens_by_kind(plan, w)
+    per_tok = 4 * g.num_kv_heads * g.head_dim
+    kern_bytes = {"attn_stream_w1": tok[1] * per_tok, "attn_stream_w4": tok[4] * per_tok}
+    res = {
+        "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "layers_rotated": len(pools),
+        "unique_kv_bytes": kv_bytes, "logical_kv_bytes": w.logical_kv_bytes(), "flops": w.flops(),
+        "GBps_unique": (kv_bytes + io_bytes) / ms / 1e6, "GBps_logical": (w.logical_kv_bytes() + io_bytes) / ms / 1e6,
+        "tokens_per_s_per_layer": w.B / ms * 1e3, "TFLOPs": w.flops() / ms / 1e9,
+        "frac_hbm_peak": (kv_bytes + io_bytes) / ms / 1e6 / HBM_PEAK_GBPS, "kernels": kt,
+        "kernel_kv_bytes": kern_bytes, "workspace_bytes": plan.workspace_bytes,
+        "shared_segments": plan.num_shared_segments,
+    }
+    dom = max((k for k in kt if k.startswith("attn_stream")), key=lambda k: kt[k]["avg_us"] * kt[k]["launches_per_step"])
+    ach = kern_bytes[dom] / kt[dom]["avg_us"] / 1e3
+    res["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": ach / HBM_PEAK_GBPS, "traffic": _traffic(dom, w.name)}
+    del pools, base
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_prefill(glm, w, steps, warmup):
+    import torch
+    g = w.geom
+    pool, q, tables, lens, cu = _dev(w.pool), _dev(w.q), _dev(w.block_tables), _dev(w.seq_lens), _dev(w.cu_q_lens)
+    out = torch.empty((w.sum_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    plan = glm.glm_plan_create(g, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    mq = int(w.q_lens.max())
+
+    def step(i):
+        glm.glm_attn_prefill_on_prefix(g, pool, q, out, tables, w.max_blocks, lens, cu, w.B, w.sum_q, mq, w.scale, plan, None)
+
+    ms = _time_steps(step, steps, warmup)
+    kt = _kernel_times(glm, step, min(steps, 16))
+    tf = w.flops() / ms / 1e9
+    ktf = w.flops() / kt["attn_stream_w4"]["avg_us"] / 1e6
+    return {"workload": w.name, "ms_per_step": ms, "flops": w.flops(), "TFLOPs": tf,
+            "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "kernels": kt,
+            "roofline": {"kernel": "attn_stream_w4", "bound": "mfma", "achieved": ktf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": ktf / MFMA_BF16_PEAK_TFLOPS, "traffic": _traffic("attn_stream_w4", w.name)}}
+
+
+def bench_churn(glm, W, w, steps, warmup, variants=4):
+    """One step = fork copy-on-write of partly filled last blocks + eviction of 2 % of the live blocks to a
+    staging buffer + their re-admission into other free slots + decode on the remapped tables."""
+    import torch
+    g = w.geom
+    pools = [_dev(w.pool)]
+    pools.append(pools[0].clone())
+    q, lens = _dev(w.q), _dev(w.seq_lens)
+    out = torch.empty((w.B, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    var = []
+    plan_ms = 0.0
+    for k in range(variants):
+        st = W.churn_step(w, k)
+        t0 = time.perf_counter()
+        plan = glm.glm_plan_create(g, st.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+        torch.cuda.synchronize()
+        plan_ms += (time.perf_counter() - t0) * 1e3 / variants
+        var.append(dict(st=st, plan=plan, tables=_dev(st.block_tables), fsrc=_dev(st.fork_src), fdst=_dev(st.fork_dst),
+                        fn=_dev(st.fork_ntok), ev=_dev(st.evict_ids), re=_dev(st.readmit_ids)))
+    n_re = max(v["st"].evict_ids.size for v in var)
+    staging = torch.empty((n_re,) + tuple(pools[0].shape[1:]), dtype=torch.int16, device="cuda")
+    ws = torch.empty(max(v["plan"].workspace_bytes for v in var), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        v = var[i % variants]
+        pool = pools[i % 2]
+        glm.glm_kv_fork_copy(g, pool, v["fsrc"], v["fdst"], v["fn"], v["st"].fork_src.size)
+        glm.glm_kv_gather(g, pool, v["ev"], staging, None, v["st"].evict_ids.size)
+        glm.glm_kv_gather(g, staging, None, pool, v["re"], v["st"].readmit_ids.size)
+        glm.glm_attn_decode(g, pool, q, out, v["tables"], w.max_blocks, lens, w.B, w.scale, v["plan"], ws)
+
+    ms = _time_steps(step, steps, warmup)
+    kt = _kernel_times(glm, step, min(steps, 16))
+    kv = w.unique_kv_bytes()
+    blk = g.block_bytes
+    gather_bytes = 2 * blk * sum(v["st"].evict_ids.size for v in var) / variants      # read + write per gather
+    fork_bytes = 2 * sum(int(v["st"].fork_ntok.sum()) for v in var) / variants * 2 * g.num_kv_heads * g.head_dim * 2
+    res = {"workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "unique_kv_bytes": kv,
+           "GBps_step": (kv + 2 * gather_bytes + fork_bytes) / ms / 1e6, "tokens_per_s_per_layer": w.B / ms * 1e3,
+           "kernels": kt, "gather_bytes_per_launch": gather_bytes, "fork_bytes_per_launch": fork_bytes}
+    if "kv_gather" in kt:
+        res["gather_GBps"] = gather_bytes / kt["kv_gather"]["avg_us"] / 1e3
+    if "kv_fork_copy" in kt:
+        res["fork_GBps"] = fork_bytes / kt["kv_fork_copy"]["avg_us"] / 1e3
+    dec_us = sum(kt[k]["avg_us"] * kt[k]["launches_per_step"] for k in kt if k.startswith("attn_"))
+    res["decode_us"] = dec_us
+    res["decode_GBps_unique"] = kv / dec_us / 1e3
+    return res
+
+
+def cpu_baseline(w, unit_bytes):
+    """The fp64 oracle as it stands, on the host cores, one pass over the whole decode batch."""
+    import oracle
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+    oracle.attention(w.geom, w.pool, w.q[:1], w.block_tables[:1], w.seq_lens[:1], w.scale, nthreads=1)  # load the library
+    reps = 0
+    t0 = time.perf_counter()
+    while True:
+        oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, nthreads=cores)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > 10.0 or reps >= 50:
+            break
+    return {"value": unit_bytes * reps / el / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "%d full passes of the fp64 oracle over the whole %s batch (%d branches x %d q heads, no prefix "
+                      "sharing: %.0f MB logical K/V per pass) in %.1f s; GB/s counts the same unique bytes as the GPU figure"
+                      % (reps, w.name, w.B, w.geom.num_q_heads, w.logical_kv_bytes() / 1e6, el)}
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2511_01633_amd as glm
+    import workloads as W
+    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn"}
+    torch.cuda.set_device(0)
+    extra = {}
+
+    w2 = W.llama8b_decode()
+    head = bench_decode(glm, w2, args.layers, args.steps, args.warmup)
+    line = {
+        "metric": "decode_attn_hbm_GBps", "value": head["GBps_unique"], "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama8b_decode: 1 layer, 64 branches on 4 shared 2048-token prefixes, suffix U{128..1024}+1, "
+                               "32 Q / 8 KV heads, d=128, block 16, bf16 K/V, fp32 out",
+                   "kv_pool_copies_rotated": head["layers_rotated"], "bytes_counted": "unique K/V tokens + Q + out"},
+        "frac_of_hbm_peak": head["frac_hbm_peak"], "tokens_per_s_per_layer": head["tokens_per_s_per_layer"],
+        "roofline": {k: v for k, v in head["roofline"].items() if k != "kernel"},
+        "roofline_kernel": head["roofline"]["kernel"],
+    }
+    extra["llama8b_decode"] = head
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w2, w2.unique_kv_bytes() + w2.q.nbytes + w2.B * w2.geom.num_q_heads * w2.geom.head_dim * 4)
+    del w2
+    if "prefill" in only:
+        extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(3, args.steps // 10), max(1, args.warmup // 10))
+    if "tree70b" in only:
+        extra["tree_decode_70b"] = bench_decode(glm, W.tree_decode_70b(), min(args.layers, 16), max(10, args.steps // 4),
+                                                max(2, args.warmup // 4))
+    if "churn" in only:
+        extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+    line["extra"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,7 +161,7 @@ typedef struct {
     int32_t n_mem;    /* decode: member requests; prefill: new tokens of rep; 0 = padding entry */
     int32_t row0;     /* first of the n_mem*(Hq/Hkv) rows this workgroup handles */
     int32_t slot0;    /* first partial-result slot, or -1: writes the final output itself */
-    int32_t waves;    /* waves per workgroup (16 rows each) */
+    int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 64 rows; 1: one independent wave, 16 rows */
 } glm_chunk;
 
 GLM_API int32_t glm_plan_num_chunks(const glm_plan *plan);
@@ -178,6 +178,19 @@ GLM_API size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, in
 GLM_API const char *glm_status_string(int status);
 GLM_API int glm_version(void);
 GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing HIP call on this thread */
+
+/*
+ * Optional per-kernel timing for benchmarks.  While enabled, every kernel the library launches
+ * is bracketed by two HIP events recorded on the stream it is launched on.  glm_profile_read
+ * waits for the recorded events of one kernel kind and returns their summed duration and count
+ * since the last glm_profile_reset.  Kernel ids: 0 streaming attention kernel with 1-wave
+ * workgroups, 1 the same with 4-wave workgroups, 2 split-K merge, 3 gather, 4 fork copy.
+ * Disabled by default; enabling it adds event records between kernels, so whole-call timings
+ * should be taken with it off.
+ */
+GLM_API int glm_profile_enable(int on);
+GLM_API int glm_profile_reset(void);
+GLM_API int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

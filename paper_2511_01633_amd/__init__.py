@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     glm_attn_decode, glm_attn_prefill_on_prefix, glm_kv_fork_copy, glm_kv_gather,
     glm_plan_create, glm_plan_create_host, glm_attn_workspace_bytes,
     glm_status_string, glm_version, glm_last_hip_error,
+    glm_profile_enable, glm_profile_reset, glm_profile_read, KERNEL_IDS,
 )

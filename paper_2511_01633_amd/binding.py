@@ -26,7 +26,9 @@ EXPORTS = (
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
+    "glm_profile_enable", "glm_profile_reset", "glm_profile_read",
 )
+KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4}
 
 
 class glm_geom(ctypes.Structure):
@@ -80,6 +82,8 @@ def _load() -> ctypes.CDLL:
     lib.glm_status_string.restype = ctypes.c_char_p
     lib.glm_version.restype = ctypes.c_int
     lib.glm_last_hip_error.restype = ctypes.c_int
+    lib.glm_profile_enable.argtypes = [ctypes.c_int]
+    lib.glm_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     return lib
 
 
@@ -244,3 +248,18 @@ def glm_kv_gather(g, src_base_dev, src_ids_dev, dst_base_dev, dst_ids_dev, n: in
     if check:
         _check(st, "glm_kv_gather")
     return st
+
+
+def glm_profile_enable(on: bool) -> None:
+    _check(_lib.glm_profile_enable(1 if on else 0), "glm_profile_enable")
+
+
+def glm_profile_reset() -> None:
+    _check(_lib.glm_profile_reset(), "glm_profile_reset")
+
+
+def glm_profile_read(kernel_id: int):
+    """(total milliseconds, launches) of one kernel kind since the last reset."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(_lib.glm_profile_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)), "glm_profile_read")
+    return ms.value, n.value

@@ -303,14 +303,269 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Wave-private streaming kernel: the decode path for work items of at most 16 query rows.
+//
+// Every wave is an independent worker (four per workgroup, no workgroup barrier) that walks
+// its own run of blocks in 32-token tiles:
+//   K goes straight from HBM into the MFMA A-operand registers (lane = token row, 16 B = 8 of
+//   the 32 contraction slots of a k-step) - no LDS hop.
+//   V is loaded coalesced, written to a wave-private LDS tile and read back transposed.
+// The loads of the next tile are issued as soon as the QK^T MFMAs and the LDS writes of the
+// current tile have consumed the staging registers, so they fly during the softmax and the
+// PV MFMAs of this wave and during everything the other waves of the SIMD do.
+// The arithmetic is the same as in the cooperative kernel above.
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) {
+    constexpr int VSTR = D + 16;
+    constexpr int KS = D / 32;
+    constexpr int DT = D / 16;
+    constexpr int VPL = 16 * D / 8 / 64;   // 16-byte V pieces per lane per block
+
+    __shared__ __attribute__((aligned(16))) __bf16 v_lds_all[4][32 * VSTR];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n16 = lane & 15;
+    const int g4 = lane >> 4;
+    __bf16 *v_lds = v_lds_all[wave];
+
+    glm_chunk c;
+    int kvh;
+    const int G = a.G;
+    if (a.mode == kPlanned) {
+        const int L = blockIdx.x;
+        const int x = L % kXcds, k = L / kXcds;
+        kvh = k % a.Hkv;
+        const glm_chunk *cp = a.chunks + (((k / a.Hkv) * kXcds + x) * 4 + wave);
+        c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
+        c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
+        c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
+        c.mem_off = __builtin_amdgcn_readfirstlane(cp->mem_off);
+        c.n_mem = __builtin_amdgcn_readfirstlane(cp->n_mem);
+        c.row0 = __builtin_amdgcn_readfirstlane(cp->row0);
+        c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
+        if (c.n_mem == 0) return;
+    } else {
+        int64_t I = (int64_t)blockIdx.x * 4 + wave;
+        kvh = (int)(I % a.Hkv); I /= a.Hkv;
+        const int rt = (int)(I % a.row_tiles); I /= a.row_tiles;
+        const int s = (int)(I % a.n_split);
+        const int64_t r = I / a.n_split;
+        if (r >= a.B) return;
+        c.rep = (int)r;
+        c.b0 = s * a.chunk_blocks;
+        c.b1 = (s == a.n_split - 1) ? INT32_MAX : (s + 1) * a.chunk_blocks;
+        c.mem_off = -1;
+        c.n_mem = 1;
+        c.row0 = rt * 16;
+        c.slot0 = (int)r * a.n_split + s;
+        if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
+    }
+
+    const int rho = c.row0 + n16;
+    const bool valid = rho < c.n_mem * G;
+    const int mi = rho / G, gh = rho - mi * G;
+    int64_t q_row = 0;
+    int limit = 0;
+    if (valid) {
+        const int r = c.mem_off < 0 ? c.rep : a.members[c.mem_off + mi];
+        q_row = r;
+        limit = a.seq_lens[r];
+    }
+    const int head = kvh * G + gh;
+    int wv_lim = __builtin_amdgcn_readfirstlane(wave_max(limit));
+    int end_blk = (wv_lim + kBlockSize - 1) / kBlockSize;
+    end_blk = min(min(end_blk, c.b1), a.max_blocks);
+    wv_lim = min(wv_lim, end_blk * kBlockSize);           // no row of this wave sees a position at or beyond this
+    const int lim_eff = min(limit, end_blk * kBlockSize);
+    const int nblk = end_blk - c.b0;
+    const int ntiles = nblk > 0 ? (nblk + 1) >> 1 : 0;
+
+    const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
+    const int64_t slab = (int64_t)kBlockSize * D;
+    const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
+    const int last_blk = end_blk - 1;
+    const __bf16 *pool_head = a.pool + (int64_t)kvh * slab;   // K slab of this head in block 0
+    const int k_off = n16 * D + 8 * g4;                       // this lane's element offset inside a K slab
+    const int v_off = lane * 8;                               // and inside a V slab
+
+    struct Tile {
+        bf16x8 k[2][KS];
+        u32x4 v[2][VPL];
+    };
+    auto load_tile = [&](Tile &T, int t) {
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb) {
+            const int bi = min(c.b0 + 2 * t + bb, last_blk);
+            const int id = min(max(__builtin_amdgcn_readfirstlane(table[bi]), 0), a.num_blocks - 1);
+            const __bf16 *kb = pool_head + (int64_t)id * blk_elems;
+            const __bf16 *vb = kb + (int64_t)a.Hkv * slab;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) T.k[bb][ks] = *reinterpret_cast<const bf16x8 *>(kb + k_off + 32 * ks);
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) T.v[bb][i] = *reinterpret_cast<const u32x4 *>(vb + v_off + 512 * i);
+        }
+    };
+
+    bf16x8 qreg[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        if (valid) {
+            qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 32 * s + 8 * g4);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
+        }
+    }
+    f32x4 acc[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY;
+    float l_run = 0.f;
+
+    // LDS addresses of this lane: where its V pieces go, and where its transposed reads start
+    int v_wr[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int p = lane + 64 * i;
+        v_wr[i] = (p / (D / 8)) * VSTR + (p % (D / 8)) * 8;
+    }
+    const __bf16 *v_rd = &v_lds[(4 * g4 + (n16 >> 2)) * VSTR + 4 * (n16 & 3)];
+
+    // One tile: consume the staging registers of T (V to LDS, K into the QK^T MFMAs), refill them with
+    // tile `next` if there is one, then softmax and PV while those loads are in flight.
+    auto step = [&](Tile &T, int t, bool refill, int next) {
+        const int pos0 = (c.b0 + 2 * t) * kBlockSize;
+        // the transposed reads of the previous tile must be done before its rows are overwritten
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (pos0 + 32 > wv_lim) {
+            // last tile: V rows nobody can see must be finite (weight 0 times NaN is NaN)
+#pragma unroll
+            for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) {
+                    const int row = bb * 16 + (lane + 64 * i) / (D / 8);
+                    u32x4 v = T.v[bb][i];
+                    if (pos0 + row >= wv_lim) v = u32x4{0u, 0u, 0u, 0u};
+                    *reinterpret_cast<u32x4 *>(&v_lds[bb * 16 * VSTR + v_wr[i]]) = v;
+                }
+        } else {
+#pragma unroll
+            for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                for (int i = 0; i < VPL; ++i)
+                    *reinterpret_cast<u32x4 *>(&v_lds[bb * 16 * VSTR + v_wr[i]]) = T.v[bb][i];
+        }
+        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.k[0][ks], qreg[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.k[1][ks], qreg[ks], s1, 0, 0, 0);
+        }
+        if (refill) load_tile(T, next);                   // the staging registers are free again
+
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = s0[i] * a.scale_log2; x[4 + i] = s1[i] * a.scale_log2; }
+        if (pos0 + 32 > lim_eff) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (pos0 + 4 * g4 + i >= lim_eff) x[i] = -INFINITY;
+                if (pos0 + 16 + 4 * g4 + i >= lim_eff) x[4 + i] = -INFINITY;
+            }
+        }
+        float m_tile = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        const float m_new = fmaxf(m_run, m_tile);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        if (__any(m_new > m_run)) {                        // some row's running maximum moved: rescale
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) acc[dt] *= alpha;
+        }
+        m_run = m_new;
+        bf16x8 p_hi, p_lo;
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float p = __builtin_amdgcn_exp2f(x[j] - m_use);
+            const __bf16 h = (__bf16)p;
+            const float hf = (float)h;
+            const __bf16 l = (__bf16)(p - hf);
+            p_hi[j] = h;
+            p_lo[j] = l;
+            psum += hf + (float)l;
+        }
+        l_run += psum;
+        // V rows written by other lanes of this wave are read below
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(v_rd + 16 * dt));
+            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(v_rd + 16 * dt + 16 * VSTR));
+            const s16x8 r01 = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 vt = __builtin_bit_cast(bf16x8, r01);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, acc[dt], 0, 0, 0);
+        }
+    };
+
+    // Two tiles are kept in flight.  The steady-state loop refills unconditionally, so the wait
+    // counts the compiler derives let the younger tile's loads stay outstanding across a step.
+    Tile ta, tb;
+    if (ntiles >= 2) {
+        load_tile(ta, 0);
+        load_tile(tb, 1);
+        int t = 0;
+        for (; t + 3 < ntiles; t += 2) {
+            step(ta, t, true, t + 2);
+            step(tb, t + 1, true, t + 3);
+        }
+        const bool three = (ntiles - t) == 3;
+        step(ta, t, three, t + 2);
+        step(tb, t + 1, false, 0);
+        if (three) step(ta, t + 2, false, 0);
+    } else if (ntiles == 1) {
+        load_tile(ta, 0);
+        step(ta, 0, false, 0);
+    }
+
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (!valid) return;
+    if (c.slot0 >= 0) {
+        const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
+        if (g4 == 0) {
+            a.part_ml[slot * 2] = m_run;
+            a.part_ml[slot * 2 + 1] = l_run;
+        }
+        float *dst = a.part_acc + slot * D + 4 * g4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt];
+    } else {
+        const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+        float *dst = a.out + (q_row * a.Hq + head) * D + 4 * g4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt] * inv;
+    }
+}
+
 // Combines a request's partial results in list order:
 //   M = max m_i,  l = sum l_i 2^(m_i-M),  out = sum acc_i 2^(m_i-M) / l.
 template <int D>
 __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
     const int r = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x;
     constexpr int E = D / 64;
-    float *dst = a.out + ((int64_t)r * a.Hq + h) * D + tid * E;
+    float *dst = a.out + ((int64_t)r * a.Hq + h) * D + lane * E;
     int n, first = 0;
     const int32_t *slots = nullptr;
     if (a.merge_kind) {
@@ -328,22 +583,51 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
         n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
         first = r * a.n_split;
     }
-    float M = -INFINITY;
-    for (int i = 0; i < n; ++i) {
-        const int64_t s = ((int64_t)(slots ? slots[i] : first + i)) * a.Hq + h;
-        M = fmaxf(M, a.part_ml[s * 2]);
-    }
-    float l = 0.f, o[E];
+    float M = -INFINITY, l = 0.f, o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
-    if (M != -INFINITY) {
-        for (int i = 0; i < n; ++i) {
-            const int64_t s = ((int64_t)(slots ? slots[i] : first + i)) * a.Hq + h;
-            const float w = __builtin_amdgcn_exp2f(a.part_ml[s * 2] - M);
-            l += a.part_ml[s * 2 + 1] * w;
-            const float *src = a.part_acc + s * D + tid * E;
+    // 64 partials at a time: lane i fetches (m, l) of partial i, so the fetches overlap; the
+    // running maximum M carries over between groups and the order of accumulation is fixed
+    for (int base = 0; base < n; base += 64) {
+        const int cnt = min(64, n - base);
+        int64_t my_slot = 0;
+        float my_m = -INFINITY, my_l = 0.f;
+        if (lane < cnt) {
+            my_slot = ((int64_t)(slots ? slots[base + lane] : first + base + lane)) * a.Hq + h;
+            my_m = a.part_ml[my_slot * 2];
+            my_l = a.part_ml[my_slot * 2 + 1];
+        }
+        float gm = my_m;
 #pragma unroll
-            for (int e = 0; e < E; ++e) o[e] += src[e] * w;
+        for (int off = 32; off >= 1; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off));
+        const float M_new = fmaxf(M, gm);
+        if (M_new == -INFINITY) continue;                  // nothing visible so far
+        const float rescale = __builtin_amdgcn_exp2f(M - M_new);
+        M = M_new;
+        l *= rescale;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] *= rescale;
+        const float my_w = __builtin_amdgcn_exp2f(my_m - M);   // 0 for lanes without a partial
+        float lw = my_l * my_w;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
+        l += lw;
+        const int lo32 = (int)(my_slot & 0xffffffff), hi32 = (int)(my_slot >> 32);
+        for (int i0 = 0; i0 < cnt; i0 += 8) {               // 8 independent fetches in flight at a time
+            float v[8][E], w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = min(i0 + j, cnt - 1);
+                const int64_t s = ((int64_t)__shfl(hi32, i) << 32) | (uint32_t)__shfl(lo32, i);
+                w[j] = (i0 + j < cnt) ? __shfl(my_w, i) : 0.f;
+                const float *src = a.part_acc + s * D + lane * E;
+#pragma unroll
+                for (int e = 0; e < E; ++e) v[j][e] = src[e];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int e = 0; e < E; ++e) o[e] += (i0 + j < cnt) ? v[j][e] * w[j] : 0.f;
         }
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
@@ -372,13 +656,24 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <int W>
 hipError_t launch_stream(int D, const AttnArgs &args, int grid, hipStream_t st) {
     if (grid <= 0) return hipSuccess;
+    ProfileScope prof(W == 1 ? kKernelStream1 : kKernelStream4, st);
     if (D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, W>), dim3(grid), dim3(64 * W), 0, st, args);
     else hipLaunchKernelGGL((attn_stream_kernel<64, W>), dim3(grid), dim3(64 * W), 0, st, args);
     return hipGetLastError();
 }
 
+hipError_t launch_private(int D, const AttnArgs &args, int64_t grid, hipStream_t st) {
+    if (grid <= 0) return hipSuccess;
+    if (grid > INT32_MAX) return hipErrorInvalidConfiguration;
+    ProfileScope prof(kKernelStream1, st);
+    if (D == 128) hipLaunchKernelGGL((attn_private_kernel<128>), dim3((unsigned)grid), dim3(256), 0, st, args);
+    else hipLaunchKernelGGL((attn_private_kernel<64>), dim3((unsigned)grid), dim3(256), 0, st, args);
+    return hipGetLastError();
+}
+
 hipError_t launch_merge(int D, const MergeArgs &m, int grid, hipStream_t st) {
     if (grid <= 0) return hipSuccess;
+    ProfileScope prof(kKernelMerge, st);
     if (D == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(grid), dim3(64), 0, st, m);
     else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(grid), dim3(64), 0, st, m);
     return hipGetLastError();
@@ -493,20 +788,16 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
         e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
         if (e == hipSuccess) {
             a.chunks = plan->d.chunks[0];
-            e = launch_stream<1>(D, a, plan->d.n_chunks[0] * Hkv, st);
+            e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
         }
         m.merge_off = plan->d.merge_off;
         m.merge_slots = plan->d.merge_slots;
         m.merge_kind = plan->d.merge_kind;
     } else {
         a.mode = kImplicitDecode;
-        if (G > kRowsPerWave) {
-            a.row_tiles = (G + kRowsPerWave * kBigWaves - 1) / (kRowsPerWave * kBigWaves);
-            e = launch_stream<kBigWaves>(D, a, B * a.n_split * a.row_tiles * Hkv, st);
-        } else {
-            a.row_tiles = 1;
-            e = launch_stream<1>(D, a, B * a.n_split * Hkv, st);
-        }
+        a.row_tiles = (G + kRowsPerWave - 1) / kRowsPerWave;
+        const int64_t items = (int64_t)B * a.n_split * a.row_tiles * Hkv;
+        e = launch_private(D, a, (items + 3) / 4, st);
         m.n_split = a.n_split;
         m.chunk_blocks = a.chunk_blocks;
     }

@@ -102,6 +102,7 @@ int glm_kv_gather(glm_geom g, const void *src_base_dev, const int32_t *src_ids_d
         const int32_t cnt = std::min<int32_t>(65535, n - done);
         const int64_t off_s = src_ids_dev ? 0 : (int64_t)done * pieces;
         const int64_t off_d = dst_ids_dev ? 0 : (int64_t)done * pieces;
+        ProfileScope prof(kKernelGather, st);
         hipLaunchKernelGGL(gather_kernel, dim3(gx, cnt), dim3(kCopyThreads), 0, st,
                            (const u32x4 *)src_base_dev + off_s, src_ids_dev ? src_ids_dev + done : nullptr,
                            (u32x4 *)dst_base_dev + off_d, dst_ids_dev ? dst_ids_dev + done : nullptr, pieces);
@@ -132,6 +133,7 @@ int glm_kv_fork_copy(glm_geom g, void *kv_pool_dev, const int32_t *src_ids_dev, 
     const int64_t pieces = 2LL * g.num_kv_heads * g.block_size * row_pieces;
     for (int32_t done = 0; done < n_pairs; done += 65535) {
         const int32_t cnt = std::min<int32_t>(65535, n_pairs - done);
+        ProfileScope prof(kKernelFork, st);
         hipLaunchKernelGGL(fork_copy_kernel, dim3(2 * g.num_kv_heads, cnt), dim3(kCopyThreads), 0, st,
                            (u32x4 *)kv_pool_dev, src_ids_dev + done, dst_ids_dev + done, n_tokens_dev + done, row_pieces,
                            pieces, g.num_blocks);

@@ -28,6 +28,23 @@ struct DevicePlan {                   // pointers into the plan's single device 
     const int32_t *merge_kind = nullptr;  // [B]
 };
 
+// Kernel ids of glm_profile_read.
+enum KernelId : int { kKernelStream1 = 0, kKernelStream4 = 1, kKernelMerge = 2, kKernelGather = 3, kKernelFork = 4 };
+
+// Brackets one kernel launch with events on its stream while profiling is enabled.
+class ProfileScope {
+public:
+    ProfileScope(int id, hipStream_t st);
+    ~ProfileScope();
+    ProfileScope(const ProfileScope &) = delete;
+    ProfileScope &operator=(const ProfileScope &) = delete;
+private:
+    hipStream_t st_;
+    hipEvent_t start_ = nullptr, stop_ = nullptr;
+    int id_;
+    bool active_ = false;
+};
+
 int set_hip_error(hipError_t e);      // records e for glm_last_hip_error, returns GLM_ERR_HIP
 int check_geom(const glm_geom &g);
 bool validate_enabled();

@@ -81,10 +81,20 @@ void build_segments(const int32_t *tables, int32_t max_blocks, const std::vector
     }
 }
 
-struct Work {
-    glm_chunk c;
-    int64_t cost;
+struct Work {            // what one workgroup does: 1 cooperative chunk, or 4 wave-private items
+    glm_chunk c[4];
+    int n;
+    int64_t cost;        // time: blocks streamed, summed over the waves
+    int64_t bytes;       // HBM traffic: distinct blocks this workgroup is the first to read
+    int32_t group;       // workgroups that stream the same K/V share a group and stay on one XCD
 };
+
+glm_chunk padding_chunk() {
+    glm_chunk pad{};
+    pad.n_mem = 0;
+    pad.slot0 = -1;
+    return pad;
+}
 
 int env_int(const char *name, int dflt) {
     const char *s = std::getenv(name);
@@ -92,35 +102,87 @@ int env_int(const char *name, int dflt) {
     return std::atoi(s);
 }
 
-// Deals the work of one launch onto the 8 XCDs: neighbours in `w` (which share K/V) stay on
-// one XCD, each XCD gets about the same cost, and inside an XCD the costly items go first.
-std::vector<glm_chunk> deal_to_xcds(std::vector<Work> &w) {
+// Deals the workgroups of one launch onto the 8 XCDs (workgroup i runs on XCD i % 8).  Each XCD
+// has its own L2 and its own share of the fabric bandwidth, so both the time and the HBM bytes
+// are balanced: groups are placed, costliest first, on the XCD where the larger of the two
+// relative loads stays smallest.  Inside an XCD the costly workgroups go first.
+std::vector<glm_chunk> deal_to_xcds(std::vector<Work> &w, int per_group) {
     std::vector<glm_chunk> out;
     if (w.empty()) return out;
-    int64_t total = 0;
-    for (auto &x : w) total += x.cost;
-    std::vector<std::vector<Work>> per(kXcds);
-    int64_t acc = 0;
-    size_t xcd = 0;
-    for (auto &x : w) {
-        // boundary k sits at total*k/8; an item goes to the XCD its midpoint falls in
-        const int64_t mid = acc + x.cost / 2;
-        size_t want = (size_t)std::min<int64_t>(kXcds - 1, total > 0 ? mid * kXcds / total : 0);
-        if (want > xcd) xcd = want;
-        per[xcd].push_back(x);
-        acc += x.cost;
+    struct Group { std::vector<size_t> items; int64_t cost = 0, bytes = 0; };
+    std::vector<Group> groups;
+    std::vector<int32_t> slot_of;
+    for (size_t i = 0; i < w.size(); ++i) {
+        const int32_t g = w[i].group;
+        if (g >= (int32_t)slot_of.size()) slot_of.resize(g + 1, -1);
+        if (slot_of[g] < 0) { slot_of[g] = (int32_t)groups.size(); groups.emplace_back(); }
+        Group &gr = groups[slot_of[g]];
+        gr.items.push_back(i);
+        gr.cost += w[i].cost;
+        gr.bytes += w[i].bytes;
+    }
+    int64_t total_cost = 1, total_bytes = 1;
+    for (auto &g : groups) { total_cost += g.cost; total_bytes += g.bytes; }
+    std::vector<size_t> order(groups.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+        if (groups[a].cost != groups[b].cost) return groups[a].cost > groups[b].cost;
+        return groups[a].bytes > groups[b].bytes;
+    });
+    std::vector<std::vector<size_t>> per(kXcds);
+    double load_cost[kXcds] = {0}, load_bytes[kXcds] = {0};
+    for (size_t gi : order) {
+        const Group &g = groups[gi];
+        int best = 0;
+        double best_v = 1e300;
+        for (int x = 0; x < kXcds; ++x) {
+            const double v = std::max((load_cost[x] + g.cost) / (double)total_cost,
+                                      (load_bytes[x] + g.bytes) / (double)total_bytes);
+            if (v < best_v) { best_v = v; best = x; }
+        }
+        load_cost[best] += g.cost;
+        load_bytes[best] += g.bytes;
+        for (size_t i : g.items) per[best].push_back(i);      // already in descending cost order
     }
     size_t longest = 0;
-    for (auto &v : per) {
-        std::stable_sort(v.begin(), v.end(), [](const Work &a, const Work &b) { return a.cost > b.cost; });
-        longest = std::max(longest, v.size());
-    }
-    glm_chunk pad{};
-    pad.n_mem = 0;
-    pad.slot0 = -1;
-    out.resize(longest * kXcds, pad);
+    for (auto &v : per) longest = std::max(longest, v.size());
+    out.resize(longest * kXcds * per_group, padding_chunk());
     for (size_t x = 0; x < (size_t)kXcds; ++x)
-        for (size_t k = 0; k < per[x].size(); ++k) out[k * kXcds + x] = per[x][k].c;
+        for (size_t k = 0; k < per[x].size(); ++k)
+            for (int j = 0; j < w[per[x][k]].n; ++j) out[(k * kXcds + x) * per_group + j] = w[per[x][k]].c[j];
+    return out;
+}
+
+struct Item {
+    glm_chunk c;
+    int64_t blocks;
+    bool first;          // first row tile of its token chunk: the one that pulls the blocks from HBM
+};
+
+// Packs wave-private items four to a workgroup.  Row tiles of one shared token chunk stay
+// together (they stream the same K/V, so the later ones hit in cache); the rest is sorted by
+// cost so that the four waves of a workgroup finish together.
+std::vector<Work> pack_quads(std::vector<Item> &families, std::vector<Item> &singles) {
+    std::stable_sort(singles.begin(), singles.end(), [](const Item &a, const Item &b) { return a.blocks > b.blocks; });
+    std::vector<Work> out;
+    auto cut = [&](std::vector<Item> &v) {
+        for (size_t i = 0; i < v.size(); i += 4) {
+            Work q{};
+            q.n = (int)std::min<size_t>(4, v.size() - i);
+            q.cost = 0;
+            q.bytes = 0;
+            q.group = (int32_t)out.size();
+            for (int j = 0; j < 4; ++j) q.c[j] = padding_chunk();
+            for (int j = 0; j < q.n; ++j) {
+                q.c[j] = v[i + j].c;
+                q.cost += v[i + j].blocks;
+                if (v[i + j].first) q.bytes += v[i + j].blocks;
+            }
+            out.push_back(q);
+        }
+    };
+    cut(families);
+    cut(singles);
     return out;
 }
 
@@ -136,21 +198,26 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     std::vector<Segment> segs;
     if (B > 0) build_segments(tables, p.max_blocks, nblk, all, 0, segs);
 
-    // chunk length: aim at a few workgroups per SIMD over the whole launch
+    // Segments with many rows go to the cooperative kernel (64 rows per workgroup share one staged
+    // K/V tile); the rest is cut into wave-private items of 16 rows.
+    const int coop_min_rows = env_int("GLM_PLAN_COOP_MIN_ROWS", 128);
+    auto is_coop = [&](int64_t rows) { return rows >= coop_min_rows; };
+    // chunk length: enough work items to fill every SIMD a few times over, yet several tiles each
     int64_t units = 0;
     for (auto &s : segs) {
         const int64_t rows = (int64_t)s.members.size() * G;
-        const int waves = rows > kRowsPerWave ? kBigWaves : 1;
-        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kRowsPerWave * waves);
+        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, is_coop(rows) ? kRowsPerWave * kBigWaves : kRowsPerWave);
     }
-    const int target = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 12);
+    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 12);
     int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
     cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
     cb = (cb + 1) & ~1;   // whole 32-token tiles
     if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb = std::max(1, forced);
 
     std::vector<std::vector<int32_t>> per_req(B);
-    std::vector<Work> work[2];
+    std::vector<Work> coop;
+    std::vector<Item> families, singles;
+    int32_t n_groups = 0;
     p.members.clear();
     p.n_slots = 0;
     p.n_shared_segments = 0;
@@ -167,7 +234,8 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         const int32_t mem_off = (int32_t)p.members.size();
         p.members.insert(p.members.end(), s.members.begin(), s.members.end());
         const int64_t rows = (int64_t)nm * G;
-        const int waves = rows > kRowsPerWave ? kBigWaves : 1;
+        const bool cooperative = is_coop(rows);
+        const int waves = cooperative ? kBigWaves : 1;
         const int32_t tile_rows = kRowsPerWave * waves;
         const int32_t len = s.b1 - s.b0;
         const int32_t nc = ceil_div(len, cb);
@@ -186,6 +254,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
                 p.n_slots += nm;
                 for (int32_t mi = 0; mi < nm; ++mi) per_req[s.members[mi]].push_back(slot0 + mi);
             }
+            const int32_t group = n_groups++;
             for (int32_t row0 = 0; row0 < rows; row0 += tile_rows) {
                 glm_chunk c{};
                 c.rep = s.members[0];
@@ -196,8 +265,20 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
                 c.row0 = row0;
                 c.slot0 = slot0;
                 c.waves = waves;
-                const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), kRowsPerWave);
-                work[waves == 1 ? 0 : 1].push_back({c, (int64_t)(c1 - c0) * (4 + tiles_here)});
+                if (cooperative) {
+                    const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), kRowsPerWave);
+                    Work w{};
+                    w.c[0] = c;
+                    w.n = 1;
+                    w.cost = (int64_t)(c1 - c0) * (4 + tiles_here);
+                    w.bytes = row0 == 0 ? c1 - c0 : 0;
+                    w.group = group;
+                    coop.push_back(w);
+                } else if (rows > kRowsPerWave) {
+                    families.push_back({c, (int64_t)(c1 - c0), row0 == 0});
+                } else {
+                    singles.push_back({c, (int64_t)(c1 - c0), true});
+                }
             }
             if (last) break;
         }
@@ -212,7 +293,9 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         p.merge_slots.insert(p.merge_slots.end(), per_req[r].begin(), per_req[r].end());
     }
     p.merge_off[B] = (int32_t)p.merge_slots.size();
-    for (int k = 0; k < 2; ++k) p.chunks[k] = deal_to_xcds(work[k]);
+    std::vector<Work> quads = pack_quads(families, singles);
+    p.chunks[0] = deal_to_xcds(quads, 4);
+    p.chunks[1] = deal_to_xcds(coop, 1);
     return GLM_OK;
 }
 
@@ -237,11 +320,17 @@ int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
             c.waves = kBigWaves;
             const int64_t last_pos = std::min<int64_t>(rows, row0 + tile_rows) - 1;
             const int64_t visible = ctx + last_pos / G + 1;
-            work.push_back({c, ceil_div(visible, kBlockSize)});
+            Work wk{};
+            wk.c[0] = c;
+            wk.n = 1;
+            wk.cost = ceil_div(visible, kBlockSize);
+            wk.bytes = row0 == 0 ? wk.cost : 0;
+            wk.group = r;                       // the tiles of one request walk the same blocks
+            work.push_back(wk);
         }
     }
     p.chunks[0].clear();
-    p.chunks[1] = deal_to_xcds(work);
+    p.chunks[1] = deal_to_xcds(work, 1);
     p.members.clear();
     p.merge_off.assign(B + 1, 0);
     p.merge_slots.clear();

@@ -1,0 +1,72 @@
+// Optional per-kernel timing with HIP events recorded on the stream each kernel is launched on.
+// Off by default: the hot calls then record nothing.
+#include <mutex>
+#include <vector>
+
+#include "glm_internal.h"
+
+namespace glm {
+
+namespace {
+struct Sample { hipEvent_t start, stop; int id; };
+std::mutex g_mu;
+bool g_enabled = false;
+std::vector<Sample> g_samples;
+}  // namespace
+
+ProfileScope::ProfileScope(int id, hipStream_t st) : st_(st), id_(id) {
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        active_ = g_enabled;
+    }
+    if (!active_) return;
+    if (hipEventCreate(&start_) != hipSuccess || hipEventCreate(&stop_) != hipSuccess ||
+        hipEventRecord(start_, st_) != hipSuccess)
+        active_ = false;
+}
+
+ProfileScope::~ProfileScope() {
+    if (!active_) return;
+    if (hipEventRecord(stop_, st_) != hipSuccess) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_samples.push_back({start_, stop_, id_});
+}
+
+}  // namespace glm
+
+using namespace glm;
+
+extern "C" {
+
+int glm_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_enabled = on != 0;
+    return GLM_OK;
+}
+
+int glm_profile_reset(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (Sample &s : g_samples) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
+    g_samples.clear();
+    return GLM_OK;
+}
+
+int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    double ms = 0.0;
+    int64_t n = 0;
+    for (Sample &s : g_samples) {
+        if (s.id != kernel_id) continue;
+        hipError_t e = hipEventSynchronize(s.stop);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, s.start, s.stop);
+        if (e != hipSuccess) return set_hip_error(e);
+        ms += t;
+        ++n;
+    }
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = n;
+    return GLM_OK;
+}
+
+}  // extern "C"
