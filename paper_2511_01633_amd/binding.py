@@ -14,7 +14,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libglm.so")
+# GLM_LIBRARY_PATH points at another build of the same library (e.g. one with different compile flags)
+LIB_PATH = os.environ.get("GLM_LIBRARY_PATH") or os.path.join(_HERE, "libglm.so")
 
 GLM_OK = 0
 GLM_ERR_NULL, GLM_ERR_GEOM, GLM_ERR_ALIGN, GLM_ERR_WORKSPACE = -1, -2, -3, -4
@@ -36,7 +37,7 @@ class glm_geom(ctypes.Structure):
 
 
 class glm_chunk(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("rep", "b0", "b1", "mem_off", "n_mem", "row0", "slot0", "waves")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("rep", "b0", "b1", "mem_off", "n_mem", "row0", "slot0", "ids_off", "n_ids", "waves")]
 
 
 class GlmError(RuntimeError):
@@ -46,6 +47,12 @@ class GlmError(RuntimeError):
 
 
 def _load() -> ctypes.CDLL:
+    # torch (used for device memory and streams) must bring in its HIP runtime first, so that the
+    # library binds to the same runtime instance instead of loading a second one
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise ImportError("libglm.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "or `python paper_2511_01633_amd/build.py` (needs hipcc)")

@@ -40,6 +40,7 @@ struct AttnArgs {
     const int32_t *cu_q_lens;   // nullptr: decode
     const glm_chunk *chunks;    // planned mode
     const int32_t *members;     // planned decode
+    const int32_t *block_ids;   // planned decode: physical ids of each item's run
     float *part_ml;             // [slot][Hq][2]  (running max in log2 units, sum)
     float *part_acc;            // [slot][Hq][D]
     int32_t max_blocks, B, Hkv, Hq, G, num_blocks;
@@ -345,6 +346,8 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
         c.n_mem = __builtin_amdgcn_readfirstlane(cp->n_mem);
         c.row0 = __builtin_amdgcn_readfirstlane(cp->row0);
         c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
+        c.ids_off = __builtin_amdgcn_readfirstlane(cp->ids_off);
+        c.n_ids = __builtin_amdgcn_readfirstlane(cp->n_ids);
         if (c.n_mem == 0) return;
     } else {
         int64_t I = (int64_t)blockIdx.x * 4 + wave;
@@ -360,9 +363,51 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
         c.n_mem = 1;
         c.row0 = rt * 16;
         c.slot0 = (int)r * a.n_split + s;
+        c.ids_off = 0;
+        c.n_ids = 0;
         if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
     }
 
+    // ---- addressing that needs nothing but the work item
+    const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
+    const int32_t *ids = a.block_ids + c.ids_off;                 // the run's ids as of plan time (n_ids of them)
+    const int64_t slab = (int64_t)kBlockSize * D;
+    const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
+    const __bf16 *pool_head = a.pool + (int64_t)kvh * slab;       // K slab of this head in block 0
+    const int k_off = n16 * D + 8 * g4;                           // this lane's element offset inside a K slab
+    const int v_off = lane * 8;                                   // and inside a V slab
+    int last_blk = c.b0;                                          // set once the live lengths are known
+
+    struct Tile {
+        bf16x8 k[2][KS];
+        u32x4 v[2][VPL];
+    };
+    auto load_tile = [&](Tile &T, int t) {
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb) {
+            const int rel = 2 * t + bb;
+            int id;
+            if (rel < c.n_ids) id = ids[rel];
+            else id = table[min(c.b0 + rel, last_blk)];
+            id = min(max(__builtin_amdgcn_readfirstlane(id), 0), a.num_blocks - 1);
+            const __bf16 *kb = pool_head + (int64_t)id * blk_elems;
+            const __bf16 *vb = kb + (int64_t)a.Hkv * slab;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) T.k[bb][ks] = *reinterpret_cast<const bf16x8 *>(kb + k_off + 32 * ks);
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) T.v[bb][i] = *reinterpret_cast<const u32x4 *>(vb + v_off + 512 * i);
+        }
+    };
+
+    // Tiles that lie wholly inside the planned run are requested before anything else is known:
+    // their addresses need one dependent fetch (the id list) instead of the chain
+    // members -> lengths -> table -> K/V.
+    Tile ta, tb;
+    const int early = min(c.n_ids >> 1, 2);
+    if (early >= 1) load_tile(ta, 0);
+    if (early >= 2) load_tile(tb, 1);
+
+    // ---- this lane's query row and the live lengths
     const int rho = c.row0 + n16;
     const bool valid = rho < c.n_mem * G;
     const int mi = rho / G, gh = rho - mi * G;
@@ -381,32 +426,7 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
     const int lim_eff = min(limit, end_blk * kBlockSize);
     const int nblk = end_blk - c.b0;
     const int ntiles = nblk > 0 ? (nblk + 1) >> 1 : 0;
-
-    const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
-    const int64_t slab = (int64_t)kBlockSize * D;
-    const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
-    const int last_blk = end_blk - 1;
-    const __bf16 *pool_head = a.pool + (int64_t)kvh * slab;   // K slab of this head in block 0
-    const int k_off = n16 * D + 8 * g4;                       // this lane's element offset inside a K slab
-    const int v_off = lane * 8;                               // and inside a V slab
-
-    struct Tile {
-        bf16x8 k[2][KS];
-        u32x4 v[2][VPL];
-    };
-    auto load_tile = [&](Tile &T, int t) {
-#pragma unroll
-        for (int bb = 0; bb < 2; ++bb) {
-            const int bi = min(c.b0 + 2 * t + bb, last_blk);
-            const int id = min(max(__builtin_amdgcn_readfirstlane(table[bi]), 0), a.num_blocks - 1);
-            const __bf16 *kb = pool_head + (int64_t)id * blk_elems;
-            const __bf16 *vb = kb + (int64_t)a.Hkv * slab;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) T.k[bb][ks] = *reinterpret_cast<const bf16x8 *>(kb + k_off + 32 * ks);
-#pragma unroll
-            for (int i = 0; i < VPL; ++i) T.v[bb][i] = *reinterpret_cast<const u32x4 *>(vb + v_off + 512 * i);
-        }
-    };
+    last_blk = max(end_blk - 1, c.b0);
 
     bf16x8 qreg[KS];
 #pragma unroll
@@ -418,6 +438,7 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
             for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
         }
     }
+
     f32x4 acc[DT];
 #pragma unroll
     for (int t = 0; t < DT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -520,10 +541,9 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
 
     // Two tiles are kept in flight.  The steady-state loop refills unconditionally, so the wait
     // counts the compiler derives let the younger tile's loads stay outstanding across a step.
-    Tile ta, tb;
     if (ntiles >= 2) {
-        load_tile(ta, 0);
-        load_tile(tb, 1);
+        if (early < 1) load_tile(ta, 0);
+        if (early < 2) load_tile(tb, 1);
         int t = 0;
         for (; t + 3 < ntiles; t += 2) {
             step(ta, t, true, t + 2);
@@ -534,7 +554,7 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
         step(tb, t + 1, false, 0);
         if (three) step(ta, t + 2, false, 0);
     } else if (ntiles == 1) {
-        load_tile(ta, 0);
+        if (early < 1) load_tile(ta, 0);
         step(ta, 0, false, 0);
     }
 
@@ -784,6 +804,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
     if (plan) {
         a.mode = kPlanned;
         a.members = plan->d.members;
+        a.block_ids = plan->d.block_ids;
         a.chunks = plan->d.chunks[1];
         e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
         if (e == hipSuccess) {

@@ -208,7 +208,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         const int64_t rows = (int64_t)s.members.size() * G;
         units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, is_coop(rows) ? kRowsPerWave * kBigWaves : kRowsPerWave);
     }
-    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 12);
+    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 8);
     int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
     cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
     cb = (cb + 1) & ~1;   // whole 32-token tiles
@@ -219,6 +219,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     std::vector<Item> families, singles;
     int32_t n_groups = 0;
     p.members.clear();
+    p.block_ids.clear();
     p.n_slots = 0;
     p.n_shared_segments = 0;
     p.shared_blocks = 0;
@@ -255,6 +256,8 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
                 for (int32_t mi = 0; mi < nm; ++mi) per_req[s.members[mi]].push_back(slot0 + mi);
             }
             const int32_t group = n_groups++;
+            const int32_t ids_off = (int32_t)p.block_ids.size();
+            for (int32_t b = c0; b < c1; ++b) p.block_ids.push_back(tables[(int64_t)s.members[0] * p.max_blocks + b]);
             for (int32_t row0 = 0; row0 < rows; row0 += tile_rows) {
                 glm_chunk c{};
                 c.rep = s.members[0];
@@ -264,6 +267,8 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
                 c.n_mem = nm;
                 c.row0 = row0;
                 c.slot0 = slot0;
+                c.ids_off = ids_off;
+                c.n_ids = c1 - c0;
                 c.waves = waves;
                 if (cooperative) {
                     const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), kRowsPerWave);
@@ -404,6 +409,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
             const size_t o_c0 = append(buf, p->chunks[0]);
             const size_t o_c1 = append(buf, p->chunks[1]);
             const size_t o_mem = append(buf, p->members);
+            const size_t o_ids = append(buf, p->block_ids);
             const size_t o_off = append(buf, p->merge_off);
             const size_t o_slots = append(buf, p->merge_slots);
             const size_t o_kind = append(buf, p->merge_kind);
@@ -423,6 +429,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
                 p->d.n_chunks[0] = (int32_t)p->chunks[0].size();
                 p->d.n_chunks[1] = (int32_t)p->chunks[1].size();
                 p->d.members = (const int32_t *)(d + o_mem);
+                p->d.block_ids = (const int32_t *)(d + o_ids);
                 p->d.merge_off = (const int32_t *)(d + o_off);
                 p->d.merge_slots = (const int32_t *)(d + o_slots);
                 p->d.merge_kind = (const int32_t *)(d + o_kind);
