@@ -163,7 +163,7 @@ typedef struct {
     int32_t slot0;    /* first partial-result slot, or -1: writes the final output itself */
     int32_t ids_off;  /* offset of this run's physical block ids (copied from the tables when the plan was made) */
     int32_t n_ids;    /* how many of them; blocks appended later are looked up in the live table */
-    int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 64 rows; 1: one independent wave, 16 rows */
+    int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 128 rows; 1: one independent wave, 16 rows */
 } glm_chunk;
 
 GLM_API int32_t glm_plan_num_chunks(const glm_plan *plan);

@@ -1,20 +1,11 @@
 // Attention over a paged KV cache with shared prefix blocks: the streaming kernel, the
 // split-K merge kernel and the two C entry points (decode, prefill on a cached prefix).
 //
-// One kernel serves both calls.  A workgroup owns one work item: a run of logical blocks of
-// one representative request's table, one kv head, and up to 16*W query rows that all see
-// that run - the G = Hq/Hkv heads of every member request (decode) or of consecutive new
-// tokens (prefill).  K/V tiles of two blocks (32 tokens) are loaded once with coalesced
-// 16-byte loads, staged in LDS and shared by the W waves; each wave keeps 16 rows.
-//
-// Everything is computed transposed so that a query row lives in one lane column:
-//   S^T[token][row] = K . Q^T      v_mfma_f32_16x16x32_bf16, A = K rows read from LDS,
-//                                  B = Q^T held in registers for the whole item
-//   running max / sum per row      the 4 lanes that share a row exchange through two shuffles
-//   O^T[d][row]    += V^T . P^T    A = V^T through the LDS transpose read (ds_read_b64_tr_b16),
-//                                  B = P^T, which is exactly the register layout S^T came out in
-// P is split into a bf16 head and a bf16 remainder (two MFMAs) so that the weights keep
-// ~16 bits; the row sum is taken from the same rounded values.
+// Two streaming kernels share one formulation (see each kernel's comment): a cooperative one
+// for work items with many query rows (prefill, widely shared decode runs) and a wave-private one
+// for decode items of at most 16 rows.  Everything is computed transposed so that a query row
+// lives in one lane column; S^T comes out of the QK^T MFMA in exactly the register layout the
+// PV MFMA wants P^T in, and V^T is produced by the LDS transpose read (ds_read_b64_tr_b16).
 #include <cmath>
 #include <cstdlib>
 #include <vector>
@@ -27,6 +18,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum AttnMode : int32_t { kPlanned = 0, kImplicitDecode = 1, kImplicitPrefill = 2 };
@@ -64,26 +56,46 @@ __device__ __forceinline__ int wave_max(int v) {
     return v;
 }
 
-template <int D, int W>
-__global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
-    constexpr int NT = 64 * W;
-    constexpr int KSTR = D + 8;            // LDS row pitch of K in elements (16 B pad: conflict-free b128 row reads)
-    constexpr int VSTR = D + 16;           // LDS row pitch of V (32 B pad: conflict-free transpose reads)
-    constexpr int PPS = 16 * D / 8;        // 16-byte pieces in one (block, plane, head) slab
-    constexpr int PPT = 4 * PPS / NT;      // pieces per thread per 32-token tile (2 K + 2 V slabs)
-    constexpr int KS = D / 32;             // k-steps of S^T = K.Q^T
-    constexpr int DT = D / 16;             // 16-wide d tiles of O^T
-    static_assert(4 * PPS % NT == 0, "tile must split evenly over the threads");
+// ------------------------------------------------------------------------------------
+// Cooperative kernel: prefill on a cached prefix, and decode runs shared by >= 128 rows.
+//
+// One workgroup = 4 waves x 32 query rows that all see the same run of blocks.  K/V tiles of
+// two blocks (32 tokens) are fetched once per workgroup with coalesced 16-byte loads, staged in
+// a double-buffered LDS tile (one barrier per tile) and consumed by all four waves with
+// v_mfma_f32_32x32x16_bf16:
+//   S^T[32 tokens][32 rows] = K . Q^T    A = K rows from LDS (lane = token, 16 B = half a k-step),
+//                                         B = Q^T in registers for the whole item
+//   softmax per row                       a row is lane % 32; its two lanes exchange through one shuffle
+//   O^T[d][32 rows] += V^T . P^T          A = V^T through ds_read_b64_tr_b16, B = P^T = the registers
+//                                         S^T came out in (k-step s takes registers 8s..8s+7)
+// Two workgroups fit a CU (<= 256 VGPRs, 36 KiB LDS each), so one wave's softmax overlaps the
+// other wave's MFMAs on every SIMD.
+// P is split into bf16 head + remainder only while the run is short (<= kSplitLimit visible
+// keys): with thousands of keys the rounding of single weights averages out far below the
+// error bound, and this kernel is MFMA bound there.
+constexpr int kSplitLimit = 1024;
 
-    __shared__ __attribute__((aligned(16))) __bf16 k_lds[32 * KSTR];
-    __shared__ __attribute__((aligned(16))) __bf16 v_lds[32 * VSTR];
-    __shared__ int wave_lim[W];
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
+    constexpr int T = 32;                      // tokens per tile
+    constexpr int KSTR = D + 8;                // LDS row pitch of K in elements
+    constexpr int VSTR = D + 16;               // LDS row pitch of V
+    constexpr int KSTEPS = D / 16;             // k-steps of S^T = K.Q^T
+    constexpr int DT = D / 32;                 // 32-wide d tiles of O^T
+    constexpr int PLANE_PIECES = T * D / 8;    // 16-byte pieces of one plane of a tile
+    constexpr int BLOCK_PIECES = 16 * D / 8;
+    constexpr int PPT = 2 * PLANE_PIECES / 256;
+    static_assert(2 * PLANE_PIECES % 256 == 0, "tile must split evenly over the threads");
+
+    __shared__ __attribute__((aligned(16))) __bf16 k_lds[2][T * KSTR];
+    __shared__ __attribute__((aligned(16))) __bf16 v_lds[2][T * VSTR];
+    __shared__ int wave_lim[4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int n16 = lane & 15;             // row within the wave's 16 rows / token within a block
-    const int g4 = lane >> 4;              // which quarter of the k slots this lane holds
+    const int n32 = lane & 31;                 // row within the wave's 32 rows / token within a tile
+    const int h2 = lane >> 5;                  // which half of the k slots this lane holds
 
     // ------------------------------------------------------------------ which work item
     glm_chunk c;
@@ -95,21 +107,7 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
         kvh = k % a.Hkv;
         c = a.chunks[(k / a.Hkv) * kXcds + x];
         if (c.n_mem == 0) return;
-    } else if (a.mode == kImplicitDecode) {
-        int L = blockIdx.x;
-        kvh = L % a.Hkv; L /= a.Hkv;
-        const int rt = L % a.row_tiles; L /= a.row_tiles;
-        const int s = L % a.n_split;
-        const int r = L / a.n_split;
-        c.rep = r;
-        c.b0 = s * a.chunk_blocks;
-        c.b1 = (s == a.n_split - 1) ? INT32_MAX : (s + 1) * a.chunk_blocks;
-        c.mem_off = -1;
-        c.n_mem = 1;
-        c.row0 = rt * 16 * W;
-        c.slot0 = r * a.n_split + s;
-        if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
-    } else {
+    } else {                                   // prefill without a plan: request x row tile x kv head
         int L = blockIdx.x;
         kvh = L % a.Hkv; L /= a.Hkv;
         const int t = L % a.row_tiles;
@@ -119,13 +117,13 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
         c.b1 = INT32_MAX;
         c.mem_off = -1;
         c.n_mem = a.cu_q_lens[r + 1] - a.cu_q_lens[r];
-        c.row0 = t * 16 * W;
+        c.row0 = t * kCoopRows;
         c.slot0 = -1;
         if (c.row0 >= c.n_mem * G) return;
     }
 
     // ------------------------------------------------------------------ this lane's query row
-    const int rho = c.row0 + wave * 16 + n16;
+    const int rho = c.row0 + wave * 32 + n32;
     const bool valid = rho < c.n_mem * G;
     const int mi = rho / G, gh = rho - mi * G;
     int64_t q_row = 0;
@@ -144,38 +142,39 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
     const int head = kvh * G + gh;
 
     int wg_lim = wave_max(limit);
-    if (W > 1) {
-        if (lane == 0) wave_lim[wave] = wg_lim;
-        __syncthreads();
+    if (lane == 0) wave_lim[wave] = wg_lim;
+    __syncthreads();
 #pragma unroll
-        for (int w = 0; w < W; ++w) wg_lim = max(wg_lim, wave_lim[w]);
-    }
+    for (int w = 0; w < 4; ++w) wg_lim = max(wg_lim, wave_lim[w]);
     int end_blk = (wg_lim + kBlockSize - 1) / kBlockSize;
     end_blk = min(min(end_blk, c.b1), a.max_blocks);
-    wg_lim = min(wg_lim, end_blk * kBlockSize);         // nothing at or beyond this position is visible to any row
+    wg_lim = min(wg_lim, end_blk * kBlockSize);          // nothing at or beyond this position is visible to any row
     const int lim_eff = min(limit, end_blk * kBlockSize);
     const int nblk = end_blk - c.b0;
     const int ntiles = nblk > 0 ? (nblk + 1) >> 1 : 0;
+    const bool split = wg_lim <= kSplitLimit;
 
-    bf16x8 qreg[KS];
+    bf16x8 qreg[KSTEPS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
+    for (int s = 0; s < KSTEPS; ++s) {
         if (valid) {
-            qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 32 * s + 8 * g4);
+            qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 16 * s + 8 * h2);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
         }
     }
 
-    f32x4 acc[DT];
+    f32x16 acc[DT];
 #pragma unroll
-    for (int t = 0; t < DT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
     float m_run = -INFINITY;
-    float l_run = 0.f;      // this lane's share of the row sum (its 8 of every 32 tokens)
+    float l_run = 0.f;      // this lane's share of the row sum (its 16 of every 32 tokens)
 
     const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
-    const int64_t slab = (int64_t)kBlockSize * D;                 // elements of one (block, plane, head) slab
+    const int64_t slab = (int64_t)kBlockSize * D;
     const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
     auto phys = [&](int b) -> int64_t {
         const int bi = min(b, end_blk - 1);
@@ -187,11 +186,29 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
     auto issue_loads = [&](int64_t idA, int64_t idB) {
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
-            const int gp = tid + NT * i;
-            const int sl = gp / PPS, p = gp % PPS;               // slab 0: K blk A, 1: K blk B, 2: V blk A, 3: V blk B
-            const int64_t id = (sl & 1) ? idB : idA;
-            const __bf16 *src = a.pool + id * blk_elems + ((int64_t)(sl >> 1) * a.Hkv + kvh) * slab + p * 8;
+            const int gp = tid + 256 * i;
+            const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
+            const int64_t id = (p / BLOCK_PIECES) ? idB : idA;
+            const __bf16 *src = a.pool + id * blk_elems + ((int64_t)plane * a.Hkv + kvh) * slab + (p % BLOCK_PIECES) * 8;
             stage[i] = *reinterpret_cast<const u32x4 *>(src);
+        }
+    };
+    auto write_stage = [&](int buf, int t) {
+        const int pos0 = (c.b0 + 2 * t) * kBlockSize;
+        const bool tail = pos0 + T > wg_lim;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int gp = tid + 256 * i;
+            const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
+            const int row = p / (D / 8), ch = p % (D / 8);
+            u32x4 v = stage[i];
+            if (plane) {
+                // V rows no query row can see must be finite: their weight is 0 and 0 * NaN is NaN
+                if (tail && pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = v;
+            } else {
+                *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = v;
+            }
         }
     };
 
@@ -199,108 +216,143 @@ __global__ void __launch_bounds__(64 * W) attn_stream_kernel(const AttnArgs a) {
     if (ntiles > 0) {
         issue_loads(phys(c.b0), phys(c.b0 + 1));
         if (ntiles > 1) { idA_next = phys(c.b0 + 2); idB_next = phys(c.b0 + 3); }
+        write_stage(0, 0);
+        if (ntiles > 1) {
+            issue_loads(idA_next, idB_next);
+            if (ntiles > 2) { idA_next = phys(c.b0 + 4); idB_next = phys(c.b0 + 5); }
+        }
     }
+    __syncthreads();
+
+    // LDS offsets of this lane's transposed V reads: 16-lane group (lane >> 4) covers d columns
+    // 16*(group & 1) .. +15 of a 32-wide d tile, lane i of the group supplies row i/4, columns 4*(i%4) ..
+    const int v_rd = (4 * h2 + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
     for (int t = 0; t < ntiles; ++t) {
-        const int pos0 = (c.b0 + 2 * t) * kBlockSize;           // logical position of the tile's first token
-        const bool tail = pos0 + 32 > wg_lim;
-        __syncthreads();                                          // every wave is done reading the previous tile
-#pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int gp = tid + NT * i;
-            const int sl = gp / PPS, p = gp % PPS;
-            const int tok = p / (D / 8), ch = p % (D / 8);
-            const int row = (sl & 1) * 16 + tok;
-            u32x4 v = stage[i];
-            if (sl >= 2) {
-                // V rows no query row can see must be finite: their weight is 0 and 0 * NaN is NaN
-                if (tail && pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(&v_lds[row * VSTR + ch * 8]) = v;
-            } else {
-                *reinterpret_cast<u32x4 *>(&k_lds[row * KSTR + ch * 8]) = v;
-            }
-        }
-        __syncthreads();
+        const int cur = t & 1;
         if (t + 1 < ntiles) {
-            issue_loads(idA_next, idB_next);
-            if (t + 2 < ntiles) { idA_next = phys(c.b0 + 2 * t + 4); idB_next = phys(c.b0 + 2 * t + 5); }
-        }
-
-        // ---- S^T = K . Q^T for the two blocks of the tile
-        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&k_lds[n16 * KSTR + 32 * ks + 8 * g4]);
-            const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(&k_lds[(16 + n16) * KSTR + 32 * ks + 8 * g4]);
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[ks], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qreg[ks], s1, 0, 0, 0);
-        }
-        // lane (row n16, quarter g4) now holds tokens 4*g4+i of block A in s0[i] and of block B in s1[i]
-        float x[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { x[i] = s0[i] * a.scale_log2; x[4 + i] = s1[i] * a.scale_log2; }
-        if (pos0 + 32 > lim_eff) {                                // this row's visible range ends inside the tile
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (pos0 + 4 * g4 + i >= lim_eff) x[i] = -INFINITY;
-                if (pos0 + 16 + 4 * g4 + i >= lim_eff) x[4 + i] = -INFINITY;
+            write_stage(cur ^ 1, t + 1);       // everyone left that buffer at the barrier below
+            if (t + 2 < ntiles) {
+                issue_loads(idA_next, idB_next);
+                if (t + 3 < ntiles) { idA_next = phys(c.b0 + 2 * t + 6); idB_next = phys(c.b0 + 2 * t + 7); }
             }
         }
-        float m_tile = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16));
+        const int pos0 = (c.b0 + 2 * t) * kBlockSize;
+        const __bf16 *kt = k_lds[cur];
+        const __bf16 *vt = v_lds[cur];
+
+        // ---- S^T = K . Q^T
+        f32x16 sT;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sT[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&kt[n32 * KSTR + 16 * ks + 8 * h2]);
+            sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[ks], sT, 0, 0, 0);
+        }
+        // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = sT[i] * a.scale_log2;
+        if (pos0 + T > lim_eff) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (pos0 + 8 * (i >> 2) + 4 * h2 + (i & 3) >= lim_eff) x[i] = -INFINITY;
+        }
+        float m_tile = x[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, x[i]);
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
         const float m_new = fmaxf(m_run, m_tile);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        if (__any(m_new > m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+        }
         m_run = m_new;
-        bf16x8 p_hi, p_lo;
-        float psum = 0.f;
+        float p[16];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = __builtin_amdgcn_exp2f(x[j] - m_use);
-            const __bf16 h = (__bf16)p;
-            const float hf = (float)h;
-            const __bf16 l = (__bf16)(p - hf);
-            p_hi[j] = h;
-            p_lo[j] = l;
-            psum += hf + (float)l;
-        }
-        l_run = l_run * alpha + psum;
+        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(x[i] - m_use);
+        bf16x8 p_hi[2];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) acc[dt] *= alpha;
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) p_hi[s][j] = (__bf16)p[8 * s + j];
 
-        // ---- O^T += V^T . P^T
+        if (split) {
+            bf16x8 p_lo[2];
+            float psum = 0.f;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const __bf16 *va = &v_lds[(4 * g4 + (n16 >> 2)) * VSTR + 16 * dt + 4 * (n16 & 3)];
-            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)(va));
-            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)(va + 16 * VSTR));
-            const s16x8 r01 = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8 vt = __builtin_bit_cast(bf16x8, r01);
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, acc[dt], 0, 0, 0);
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, acc[dt], 0, 0, 0);
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float hf = (float)p_hi[s][j];
+                    const __bf16 l = (__bf16)(p[8 * s + j] - hf);
+                    p_lo[s][j] = l;
+                    psum += hf + (float)l;
+                }
+            l_run += psum;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const __bf16 *va = vt + v_rd + (16 * s) * VSTR + 32 * dt;
+                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
+                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
+                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[s], acc[dt], 0, 0, 0);
+                }
+        } else {
+            float psum = 0.f;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) psum += (float)p_hi[s][j];
+            l_run += psum;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const __bf16 *va = vt + v_rd + (16 * s) * VSTR + 32 * dt;
+                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
+                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
+                }
         }
+        __syncthreads();                       // tile t is consumed; its buffer may be overwritten next round
     }
 
-    l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (!valid) return;
+    // acc[dt][i] is d = 32*dt + 8*(i/4) + 4*h2 + i%4 of row n32
     if (c.slot0 >= 0) {
         const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
-        if (g4 == 0) {
+        if (h2 == 0) {
             a.part_ml[slot * 2] = m_run;
             a.part_ml[slot * 2 + 1] = l_run;
         }
-        float *dst = a.part_acc + slot * D + 4 * g4;
+        float *dst = a.part_acc + slot * D + 4 * h2;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt];
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<f32x4 *>(dst + 32 * dt + 8 * q4) =
+                    f32x4{acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
     } else {
         const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
-        float *dst = a.out + (q_row * a.Hq + head) * D + 4 * g4;
+        float *dst = a.out + (q_row * a.Hq + head) * D + 4 * h2;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(dst + 16 * dt) = acc[dt] * inv;
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<f32x4 *>(dst + 32 * dt + 8 * q4) =
+                    f32x4{acc[dt][4 * q4] * inv, acc[dt][4 * q4 + 1] * inv, acc[dt][4 * q4 + 2] * inv, acc[dt][4 * q4 + 3] * inv};
     }
 }
 
@@ -673,12 +725,12 @@ namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int W>
-hipError_t launch_stream(int D, const AttnArgs &args, int grid, hipStream_t st) {
+hipError_t launch_coop(int D, const AttnArgs &args, int64_t grid, hipStream_t st) {
     if (grid <= 0) return hipSuccess;
-    ProfileScope prof(W == 1 ? kKernelStream1 : kKernelStream4, st);
-    if (D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, W>), dim3(grid), dim3(64 * W), 0, st, args);
-    else hipLaunchKernelGGL((attn_stream_kernel<64, W>), dim3(grid), dim3(64 * W), 0, st, args);
+    if (grid > INT32_MAX) return hipErrorInvalidConfiguration;
+    ProfileScope prof(kKernelStream4, st);
+    if (D == 128) hipLaunchKernelGGL((attn_coop_kernel<128>), dim3((unsigned)grid), dim3(256), 0, st, args);
+    else hipLaunchKernelGGL((attn_coop_kernel<64>), dim3((unsigned)grid), dim3(256), 0, st, args);
     return hipGetLastError();
 }
 
@@ -806,7 +858,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
         a.members = plan->d.members;
         a.block_ids = plan->d.block_ids;
         a.chunks = plan->d.chunks[1];
-        e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
+        e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
         if (e == hipSuccess) {
             a.chunks = plan->d.chunks[0];
             e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
@@ -860,15 +912,15 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
     if (plan) {
         a.mode = kPlanned;
         a.chunks = plan->d.chunks[1];
-        e = launch_stream<kBigWaves>(D, a, plan->d.n_chunks[1] * Hkv, st);
+        e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
     } else {
         if (max_q_len == 0) return GLM_OK;
         a.mode = kImplicitPrefill;
-        const int64_t tiles = ((int64_t)max_q_len * G + kRowsPerWave * kBigWaves - 1) / (kRowsPerWave * kBigWaves);
+        const int64_t tiles = ((int64_t)max_q_len * G + kCoopRows - 1) / kCoopRows;
         const int64_t grid = tiles * B * Hkv;
         if (grid > INT32_MAX) return GLM_ERR_GEOM;
         a.row_tiles = (int32_t)tiles;
-        e = launch_stream<kBigWaves>(D, a, (int)grid, st);
+        e = launch_coop(D, a, grid, st);
     }
     return e == hipSuccess ? GLM_OK : set_hip_error(e);
 }

@@ -11,7 +11,8 @@ namespace glm {
 constexpr int kBlockSize = 16;        // tokens per KV block = one MFMA M tile
 constexpr int kXcds = 8;              // L2 domains of the chip; workgroup i runs on XCD i % 8
 constexpr int kRowsPerWave = 16;      // query rows (MFMA N) one wave owns
-constexpr int kBigWaves = 4;          // waves of a workgroup that shares staged K/V over 64 rows
+constexpr int kBigWaves = 4;          // waves of a cooperative workgroup
+constexpr int kCoopRows = 128;        // query rows of a cooperative workgroup (32 per wave)
 constexpr int kMaxImplicitSplits = 32;
 
 enum PlanKind : int32_t { kDecode = 0, kPrefill = 1 };

@@ -206,7 +206,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     int64_t units = 0;
     for (auto &s : segs) {
         const int64_t rows = (int64_t)s.members.size() * G;
-        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, is_coop(rows) ? kRowsPerWave * kBigWaves : kRowsPerWave);
+        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, is_coop(rows) ? kCoopRows : kRowsPerWave);
     }
     const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 8);
     int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
@@ -237,7 +237,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         const int64_t rows = (int64_t)nm * G;
         const bool cooperative = is_coop(rows);
         const int waves = cooperative ? kBigWaves : 1;
-        const int32_t tile_rows = kRowsPerWave * waves;
+        const int32_t tile_rows = cooperative ? kCoopRows : kRowsPerWave;
         const int32_t len = s.b1 - s.b0;
         const int32_t nc = ceil_div(len, cb);
         // spread the blocks evenly over the nc chunks, in whole tiles of 2 blocks
@@ -271,7 +271,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
                 c.n_ids = c1 - c0;
                 c.waves = waves;
                 if (cooperative) {
-                    const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), kRowsPerWave);
+                    const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), 32);
                     Work w{};
                     w.c[0] = c;
                     w.n = 1;
@@ -306,7 +306,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
 
 int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
     const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
-    const int32_t tile_rows = kRowsPerWave * kBigWaves;
+    const int32_t tile_rows = kCoopRows;
     std::vector<Work> work;
     for (int32_t r = 0; r < B; ++r) {
         if (q_lens[r] < 0 || seq_lens[r] < q_lens[r] || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks)

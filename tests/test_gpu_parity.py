@@ -268,7 +268,10 @@ def test_tree_decode_70b_full_sampled():
     ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head)
     _check(got[req, head], ref, "tree_decode_70b (256 sampled rows)")
     got_np = dw.decode(plan=None)
-    assert np.abs(got_np - got).max() <= 1e-5
+    # the 2048-row root and the 256-row sub-query prefixes run on the cooperative kernel, which
+    # keeps P in plain bf16 beyond 1024 visible keys: plan and no-plan agree to ~1e-4, not 1e-5
+    assert np.abs(got_np - got).max() <= 5e-4
+    _check(got_np[req, head], ref, "tree_decode_70b without a plan (256 sampled rows)")
 
 
 def test_eviction_churn_step_full_sampled():

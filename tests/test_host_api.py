@@ -100,7 +100,7 @@ def test_decode_plan_covers_every_block_once_and_finds_the_tree():
     for c in plan.chunks():
         if c.n_mem == 0:
             continue
-        tile = 16 * c.waves
+        tile = 128 if c.waves == 4 else 16
         mem = members[c.mem_off:c.mem_off + c.n_mem]
         lo_row, hi_row = c.row0, min(c.n_mem * G, c.row0 + tile)
         for rho in range(lo_row, hi_row):
@@ -144,7 +144,7 @@ def test_prefill_plan_tiles_every_row():
         if c.n_mem == 0:
             continue
         assert c.waves == 4 and c.slot0 == -1 and c.n_mem == q_lens[c.rep]
-        for rho in range(c.row0, min(c.n_mem * 4, c.row0 + 64)):
+        for rho in range(c.row0, min(c.n_mem * 4, c.row0 + 128)):
             rows[(c.rep, rho)] = rows.get((c.rep, rho), 0) + 1
     assert all(v == 1 for v in rows.values())
     assert len(rows) == int(q_lens.sum()) * 4
