@@ -35,6 +35,8 @@ def _parse():
     ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
     ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-headline", action="store_true",
+                    help="profiling aid: run only the workloads named by --only and print their records")
     return ap.parse_args()
 
 
@@ -246,6 +248,16 @@ def main():
     only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn"}
     torch.cuda.set_device(0)
     extra = {}
+    if args.skip_headline:
+        if "prefill" in only:
+            extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(3, args.steps // 10), max(1, args.warmup // 10))
+        if "tree70b" in only:
+            extra["tree_decode_70b"] = bench_decode(glm, W.tree_decode_70b(), min(args.layers, 16), max(10, args.steps // 4),
+                                                    max(2, args.warmup // 4))
+        if "churn" in only:
+            extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+        print(json.dumps({"extra": extra}))
+        return
 
     w2 = W.llama8b_decode()
     head = bench_decode(glm, w2, args.layers, args.steps, args.warmup)

@@ -22,7 +22,8 @@
  * hipStream_t passed as void* (NULL = the null stream).
  *
  * Supported geometry: block_size 16; head_dim 64 or 128; num_q_heads a multiple of
- * num_kv_heads (q head h reads kv head h / (Hq/Hkv)).
+ * num_kv_heads (q head h reads kv head h / (Hq/Hkv)); scale must be a positive finite number
+ * (anything else is GLM_ERR_GEOM).
  */
 #ifndef GLM_H_
 #define GLM_H_

@@ -8,6 +8,7 @@
 // PV MFMA wants P^T in, and V^T is produced by the LDS transpose read (ds_read_b64_tr_b16).
 #include <cmath>
 #include <cstdlib>
+#include <type_traits>
 #include <vector>
 
 #include "glm_internal.h"
@@ -87,9 +88,9 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     constexpr int PPT = 2 * PLANE_PIECES / 256;
     static_assert(2 * PLANE_PIECES % 256 == 0, "tile must split evenly over the threads");
 
-    __shared__ __attribute__((aligned(16))) __bf16 k_lds[2][T * KSTR];
-    __shared__ __attribute__((aligned(16))) __bf16 v_lds[2][T * VSTR];
-    __shared__ int wave_lim[4];
+    __shared__ __attribute__((aligned(16))) __bf16 k_lds[3][T * KSTR];
+    __shared__ __attribute__((aligned(16))) __bf16 v_lds[3][T * VSTR];
+    __shared__ int wave_lim[4], wave_min[4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -105,7 +106,14 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         const int L = blockIdx.x;
         const int x = L % kXcds, k = L / kXcds;
         kvh = k % a.Hkv;
-        c = a.chunks[(k / a.Hkv) * kXcds + x];
+        const glm_chunk *cp = a.chunks + ((k / a.Hkv) * kXcds + x);
+        c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
+        c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
+        c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
+        c.mem_off = __builtin_amdgcn_readfirstlane(cp->mem_off);
+        c.n_mem = __builtin_amdgcn_readfirstlane(cp->n_mem);
+        c.row0 = __builtin_amdgcn_readfirstlane(cp->row0);
+        c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
         if (c.n_mem == 0) return;
     } else {                                   // prefill without a plan: request x row tile x kv head
         int L = blockIdx.x;
@@ -142,10 +150,13 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     const int head = kvh * G + gh;
 
     int wg_lim = wave_max(limit);
-    if (lane == 0) wave_lim[wave] = wg_lim;
+    int wg_min = -wave_max(valid ? -limit : -INT32_MAX);    // smallest limit among the valid rows
+    if (lane == 0) { wave_lim[wave] = wg_lim; wave_min[wave] = wg_min; }
     __syncthreads();
 #pragma unroll
-    for (int w = 0; w < 4; ++w) wg_lim = max(wg_lim, wave_lim[w]);
+    for (int w = 0; w < 4; ++w) { wg_lim = max(wg_lim, wave_lim[w]); wg_min = min(wg_min, wave_min[w]); }
+    wg_lim = __builtin_amdgcn_readfirstlane(wg_lim);
+    wg_min = __builtin_amdgcn_readfirstlane(wg_min);
     int end_blk = (wg_lim + kBlockSize - 1) / kBlockSize;
     end_blk = min(min(end_blk, c.b1), a.max_blocks);
     wg_lim = min(wg_lim, end_blk * kBlockSize);          // nothing at or beyond this position is visible to any row
@@ -178,7 +189,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
     auto phys = [&](int b) -> int64_t {
         const int bi = min(b, end_blk - 1);
-        const int id = table[bi];
+        const int id = __builtin_amdgcn_readfirstlane(table[bi]);
         return (int64_t)min(max(id, 0), a.num_blocks - 1);
     };
 
@@ -193,76 +204,86 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             stage[i] = *reinterpret_cast<const u32x4 *>(src);
         }
     };
-    auto write_stage = [&](int buf, int t) {
+    auto write_stage = [&](int buf, int t, bool maybe_tail) {
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
-        const bool tail = pos0 + T > wg_lim;
+        if (maybe_tail && pos0 + T > wg_lim) {
+            // last tile: V rows no query row can see must be finite (their weight is 0 and 0 * NaN is NaN)
 #pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int gp = tid + 256 * i;
-            const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
-            const int row = p / (D / 8), ch = p % (D / 8);
-            u32x4 v = stage[i];
-            if (plane) {
-                // V rows no query row can see must be finite: their weight is 0 and 0 * NaN is NaN
-                if (tail && pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = v;
-            } else {
-                *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = v;
+            for (int i = 0; i < PPT; ++i) {
+                const int gp = tid + 256 * i;
+                const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
+                const int row = p / (D / 8), ch = p % (D / 8);
+                u32x4 v = stage[i];
+                if (plane) {
+                    if (pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
+                    *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = v;
+                } else {
+                    *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = v;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < PPT; ++i) {
+                const int gp = tid + 256 * i;
+                const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
+                const int row = p / (D / 8), ch = p % (D / 8);
+                if (plane) *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = stage[i];
+                else *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = stage[i];
             }
         }
     };
 
-    int64_t idA_next = 0, idB_next = 0;
-    if (ntiles > 0) {
-        issue_loads(phys(c.b0), phys(c.b0 + 1));
-        if (ntiles > 1) { idA_next = phys(c.b0 + 2); idB_next = phys(c.b0 + 3); }
-        write_stage(0, 0);
-        if (ntiles > 1) {
-            issue_loads(idA_next, idB_next);
-            if (ntiles > 2) { idA_next = phys(c.b0 + 4); idB_next = phys(c.b0 + 5); }
-        }
-    }
-    __syncthreads();
+    // LDS offsets of this lane's transposed V reads.  The d columns of an O^T tile are split: lanes
+    // 0-15 of a half take columns 16*dt .. +15, lanes 16-31 take D/2 + 16*dt .. +15, which puts the
+    // two 16-lane groups on disjoint LDS banks.  Lane i of a group supplies row i/4, columns 4*(i%4) ..
+    const int v_rd = (4 * h2 + ((lane & 15) >> 2)) * VSTR + (D / 2) * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int k_rd = n32 * KSTR + 8 * h2;
 
-    // LDS offsets of this lane's transposed V reads: 16-lane group (lane >> 4) covers d columns
-    // 16*(group & 1) .. +15 of a 32-wide d tile, lane i of the group supplies row i/4, columns 4*(i%4) ..
-    const int v_rd = (4 * h2 + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-    for (int t = 0; t < ntiles; ++t) {
-        const int cur = t & 1;
-        if (t + 1 < ntiles) {
-            write_stage(cur ^ 1, t + 1);       // everyone left that buffer at the barrier below
-            if (t + 2 < ntiles) {
-                issue_loads(idA_next, idB_next);
-                if (t + 3 < ntiles) { idA_next = phys(c.b0 + 2 * t + 6); idB_next = phys(c.b0 + 2 * t + 7); }
-            }
-        }
-        const int pos0 = (c.b0 + 2 * t) * kBlockSize;
-        const __bf16 *kt = k_lds[cur];
-        const __bf16 *vt = v_lds[cur];
-
-        // ---- S^T = K . Q^T
+    // S^T = K . Q^T of the tile staged in buffer `buf`: one accumulator, KSTEPS dependent MFMAs
+    auto qk = [&](int buf) -> f32x16 {
+        const __bf16 *kt = k_lds[buf] + k_rd;
         f32x16 sT;
 #pragma unroll
         for (int i = 0; i < 16; ++i) sT[i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&kt[n32 * KSTR + 16 * ks + 8 * h2]);
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + 16 * ks);
             sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[ks], sT, 0, 0, 0);
         }
-        // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = sT[i] * a.scale_log2;
-        if (pos0 + T > lim_eff) {
+        return sT;
+    };
+
+    // Software pipeline over tiles, three LDS stages, one barrier per tile.  At the top of step t:
+    //   sT holds the raw scores of tile t (its QK^T ran during step t-1),
+    //   tile t+1 is staged in LDS, tile t+2 sits in the staging registers (its loads flew during step t-1).
+    // Step t stages tile t+2, requests tile t+3, starts QK^T of tile t+1 and, while those MFMAs run,
+    // does the softmax of tile t on the VALU; then PV of tile t.
+    // FAST steps have no masking and no conditional prefetch, so that the MFMAs of QK^T(t+1) and the
+    // exponentials of tile t share one basic block and get interleaved by the scheduler.
+    f32x16 sT;
+    int64_t idA_next = 0, idB_next = 0;
+    auto step = [&](auto fast_tag, auto split_tag, int t, int buf_t, int buf_t1, int buf_t2) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        constexpr bool SPLIT = decltype(split_tag)::value;
+        const int pos0 = (c.b0 + 2 * t) * kBlockSize;
+        if (FAST || t + 2 < ntiles) {
+            write_stage(buf_t2, t + 2, !FAST);
+            if (FAST || t + 3 < ntiles) {
+                issue_loads(idA_next, idB_next);
+                if (FAST || t + 4 < ntiles) { idA_next = phys(c.b0 + 2 * t + 8); idB_next = phys(c.b0 + 2 * t + 9); }
+            }
+        }
+        // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]; raw scores,
+        // the factor scale*log2(e) (> 0) is folded into the exponent
+        if (!FAST && pos0 + T > lim_eff) {
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                if (pos0 + 8 * (i >> 2) + 4 * h2 + (i & 3) >= lim_eff) x[i] = -INFINITY;
+                if (pos0 + 8 * (i >> 2) + 4 * h2 + (i & 3) >= lim_eff) sT[i] = -INFINITY;
         }
-        float m_tile = x[0];
+        float m_tile = sT[0];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, x[i]);
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32)) * a.scale_log2;
         const float m_new = fmaxf(m_run, m_tile);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         if (__any(m_new > m_run)) {
@@ -274,63 +295,89 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
                 for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
         }
         m_run = m_new;
+
+        f32x16 s_next = sT;
+        if (FAST || t + 1 < ntiles) s_next = qk(buf_t1);
+
         float p[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(x[i] - m_use);
-        bf16x8 p_hi[2];
+        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use));
+        bf16x8 p_hi[2], p_lo[2];
+        float psum = 0.f;
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) p_hi[s][j] = (__bf16)p[8 * s + j];
-
-        if (split) {
-            bf16x8 p_lo[2];
-            float psum = 0.f;
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float hf = (float)p_hi[s][j];
+            for (int j = 0; j < 8; ++j) {
+                const __bf16 h = (__bf16)p[8 * s + j];
+                p_hi[s][j] = h;
+                if (SPLIT) {
+                    const float hf = (float)h;
                     const __bf16 l = (__bf16)(p[8 * s + j] - hf);
                     p_lo[s][j] = l;
                     psum += hf + (float)l;
+                } else {
+                    psum += p[8 * s + j];   // > kSplitLimit keys: the rounding of single weights averages out
                 }
-            l_run += psum;
+            }
+        l_run += psum;
+        const __bf16 *vt = v_lds[buf_t] + v_rd;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const __bf16 *va = vt + v_rd + (16 * s) * VSTR + 32 * dt;
-                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
-                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
-                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[s], acc[dt], 0, 0, 0);
-                }
-        } else {
-            float psum = 0.f;
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) psum += (float)p_hi[s][j];
-            l_run += psum;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const __bf16 *va = vt + v_rd + (16 * s) * VSTR + 32 * dt;
-                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
-                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
-                }
+            for (int s = 0; s < 2; ++s) {
+                const __bf16 *va = vt + (16 * s) * VSTR + 16 * dt;
+                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
+                if (SPLIT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[s], acc[dt], 0, 0, 0);
+            }
+        sT = s_next;
+        __syncthreads();    // tile t is consumed, tile t+2 is staged: the next step may read / overwrite
+    };
+
+    auto run = [&](auto split_tag) {
+        // prologue: stage tiles 0 and 1, compute the scores of tile 0, have tile 2 in flight
+        issue_loads(phys(c.b0), phys(c.b0 + 1));
+        if (ntiles > 1) { idA_next = phys(c.b0 + 2); idB_next = phys(c.b0 + 3); }
+        write_stage(0, 0, true);
+        if (ntiles > 1) {
+            issue_loads(idA_next, idB_next);
+            if (ntiles > 2) { idA_next = phys(c.b0 + 4); idB_next = phys(c.b0 + 5); }
         }
-        __syncthreads();                       // tile t is consumed; its buffer may be overwritten next round
+        __syncthreads();
+        sT = qk(0);
+        if (ntiles > 1) {
+            write_stage(1, 1, true);
+            if (ntiles > 2) {
+                issue_loads(idA_next, idB_next);
+                if (ntiles > 3) { idA_next = phys(c.b0 + 6); idB_next = phys(c.b0 + 7); }
+            }
+        }
+        __syncthreads();
+        // tiles that end at or below every row's limit need no mask; the last four steps take the
+        // general path because their prefetches run off the end
+        const int t_nomask = max(0, (min(wg_min, end_blk * kBlockSize) - c.b0 * kBlockSize) / T);
+        const int t_fast = min(ntiles - 4, t_nomask);
+        int t = 0, b0 = 0, b1 = 1, b2 = 2;
+        for (; t < t_fast; ++t) {
+            step(std::true_type{}, split_tag, t, b0, b1, b2);
+            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
+        }
+        for (; t < ntiles; ++t) {
+            step(std::false_type{}, split_tag, t, b0, b1, b2);
+            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
+        }
+    };
+    if (ntiles > 0) {
+        if (split) run(std::true_type{});
+        else run(std::false_type{});
     }
 
     l_run += __shfl_xor(l_run, 32);
     if (!valid) return;
-    // acc[dt][i] is d = 32*dt + 8*(i/4) + 4*h2 + i%4 of row n32
+    // acc[dt][i] is row m = 8*(i/4) + 4*h2 + i%4 of O^T tile dt, which is d = 16*dt + m for m < 16 and
+    // d = D/2 + 16*dt + m - 16 otherwise (see v_rd)
     if (c.slot0 >= 0) {
         const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
         if (h2 == 0) {
@@ -342,7 +389,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<f32x4 *>(dst + 32 * dt + 8 * q4) =
+                *reinterpret_cast<f32x4 *>(dst + 16 * dt + (q4 >> 1) * (D / 2) + 8 * (q4 & 1)) =
                     f32x4{acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
     } else {
         const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
@@ -351,7 +398,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<f32x4 *>(dst + 32 * dt + 8 * q4) =
+                *reinterpret_cast<f32x4 *>(dst + 16 * dt + (q4 >> 1) * (D / 2) + 8 * (q4 & 1)) =
                     f32x4{acc[dt][4 * q4] * inv, acc[dt][4 * q4 + 1] * inv, acc[dt][4 * q4 + 2] * inv, acc[dt][4 * q4 + 3] * inv};
     }
 }
@@ -801,7 +848,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
                     float scale, const glm_plan *plan, void *workspace_dev, size_t workspace_bytes,
                     void *hip_stream) {
     if (int st = check_geom(g)) return st;
-    if (B < 0 || max_blocks <= 0) return GLM_ERR_GEOM;
+    if (B < 0 || max_blocks <= 0 || !(scale > 0.f)) return GLM_ERR_GEOM;
     if (B == 0) return GLM_OK;
     if (!kv_pool_dev || !q_dev || !out_dev || !block_tables_dev || !seq_lens_dev) return GLM_ERR_NULL;
     if (!aligned16(kv_pool_dev) || !aligned16(q_dev) || !aligned16(out_dev) || !aligned16(workspace_dev))
@@ -884,7 +931,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
                                const glm_plan *plan, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
     (void)workspace_dev; (void)workspace_bytes;
     if (int st = check_geom(g)) return st;
-    if (B < 0 || max_blocks <= 0 || sum_q < 0 || max_q_len < 0) return GLM_ERR_GEOM;
+    if (B < 0 || max_blocks <= 0 || sum_q < 0 || max_q_len < 0 || !(scale > 0.f)) return GLM_ERR_GEOM;
     if (B == 0 || sum_q == 0) return GLM_OK;
     if (!kv_pool_dev || !q_dev || !out_dev || !block_tables_dev || !seq_lens_dev || !cu_q_lens_dev) return GLM_ERR_NULL;
     if (!aligned16(kv_pool_dev) || !aligned16(q_dev) || !aligned16(out_dev)) return GLM_ERR_ALIGN;
