@@ -215,6 +215,33 @@ def bench_churn(glm, W, w, steps, warmup, variants=4):
     return res
 
 
+def reference_rates(glm):
+    """MFMA-only rate and plain-copy bandwidth of this chip, measured with the library's reference kernels."""
+    import torch
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    wgs, iters = 256 * 8, 4000
+    glm.glm_bench_mfma(sink, wgs, 100)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    glm.glm_bench_mfma(sink, wgs, iters)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    mfma_tflops = wgs * 4 * iters * 4 * 32768 / dt / 1e12
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        glm.glm_bench_copy(src, dst, n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 10
+    for _ in range(reps):
+        glm.glm_bench_copy(src, dst, n)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    return {"mfma_bf16_32x32x16_TFLOPs_measured": mfma_tflops, "copy_1GiB_GBps_read_plus_write": 2 * n / dt / 1e9}
+
+
 def cpu_baseline(w, unit_bytes):
     """The fp64 oracle as it stands, on the host cores, one pass over the whole decode batch."""
     import oracle
@@ -250,13 +277,13 @@ def main():
     extra = {}
     if args.skip_headline:
         if "prefill" in only:
-            extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(3, args.steps // 10), max(1, args.warmup // 10))
+            extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(5, args.steps // 4), max(2, args.warmup // 4))
         if "tree70b" in only:
             extra["tree_decode_70b"] = bench_decode(glm, W.tree_decode_70b(), min(args.layers, 16), max(10, args.steps // 4),
                                                     max(2, args.warmup // 4))
         if "churn" in only:
             extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
-        print(json.dumps({"extra": extra}))
+        print(json.dumps({"reference_rates": reference_rates(glm), "extra": extra}))
         return
 
     w2 = W.llama8b_decode()
@@ -277,12 +304,13 @@ def main():
         line["cpu_baseline"] = cpu_baseline(w2, w2.unique_kv_bytes() + w2.q.nbytes + w2.B * w2.geom.num_q_heads * w2.geom.head_dim * 4)
     del w2
     if "prefill" in only:
-        extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(3, args.steps // 10), max(1, args.warmup // 10))
+        extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(5, args.steps // 4), max(2, args.warmup // 4))
     if "tree70b" in only:
         extra["tree_decode_70b"] = bench_decode(glm, W.tree_decode_70b(), min(args.layers, 16), max(10, args.steps // 4),
                                                 max(2, args.warmup // 4))
     if "churn" in only:
         extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+    line["reference_rates"] = reference_rates(glm)
     line["extra"] = extra
     print(json.dumps(line))
 

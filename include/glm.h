@@ -195,6 +195,17 @@ GLM_API int glm_profile_enable(int on);
 GLM_API int glm_profile_reset(void);
 GLM_API int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches);
 
+/*
+ * Reference kernels for benchmarks (not part of the attention path).
+ * glm_bench_mfma: `workgroups` workgroups of 4 waves each issue iters*4 v_mfma_f32_32x32x16_bf16
+ *   (32768 flop per instruction per wave) and nothing else; timing it gives the bf16 matrix rate the
+ *   chip sustains at the clock it actually holds.  sink_dev: at least 4 bytes of device memory.
+ * glm_bench_copy: dst[i] = src[i] over `bytes` bytes (multiple of 16, both pointers 16-byte aligned),
+ *   a plain streaming copy of known size: the calibration point for HBM traffic counters.
+ */
+GLM_API int glm_bench_mfma(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_stream);
+GLM_API int glm_bench_copy(const void *src_dev, void *dst_dev, size_t bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = (
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
-    "glm_profile_enable", "glm_profile_reset", "glm_profile_read",
+    "glm_profile_enable", "glm_profile_reset", "glm_profile_read", "glm_bench_mfma", "glm_bench_copy",
 )
 KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4}
 
@@ -89,6 +89,8 @@ def _load() -> ctypes.CDLL:
     lib.glm_status_string.restype = ctypes.c_char_p
     lib.glm_version.restype = ctypes.c_int
     lib.glm_last_hip_error.restype = ctypes.c_int
+    lib.glm_bench_mfma.argtypes = [vp, i32, i32, vp]
+    lib.glm_bench_copy.argtypes = [vp, vp, sz, vp]
     lib.glm_profile_enable.argtypes = [ctypes.c_int]
     lib.glm_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     return lib
@@ -270,3 +272,11 @@ def glm_profile_read(kernel_id: int):
     ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(_lib.glm_profile_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)), "glm_profile_read")
     return ms.value, n.value
+
+
+def glm_bench_mfma(sink_dev, workgroups: int, iters: int, hip_stream=None) -> None:
+    _check(_lib.glm_bench_mfma(_dev(sink_dev), workgroups, iters, _stream(hip_stream)), "glm_bench_mfma")
+
+
+def glm_bench_copy(src_dev, dst_dev, nbytes: int, hip_stream=None) -> None:
+    _check(_lib.glm_bench_copy(_dev(src_dev), _dev(dst_dev), nbytes, _stream(hip_stream)), "glm_bench_copy")

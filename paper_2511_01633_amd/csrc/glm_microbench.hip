@@ -1,0 +1,69 @@
+// Two reference kernels the benchmark uses to put its figures in context: an MFMA-only loop
+// (what the matrix cores sustain at the clock the chip actually holds) and a plain streaming
+// copy of a contiguous buffer (the calibration point for the HBM traffic counters).
+#include "glm_internal.h"
+
+namespace glm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Every wave runs `iters` rounds of 4 independent v_mfma_f32_32x32x16_bf16 chains.
+__global__ void __launch_bounds__(256) mfma_peak_kernel(float *sink, int iters) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { a[j] = (__bf16)(float)(threadIdx.x & 3); b[j] = (__bf16)0.5f; }
+    f32x16 c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 0.f; c2[i] = 0.f; c3[i] = 0.f; }
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += c0[i] + c1[i] + c2[i] + c3[i];
+    if (r == -1.f) sink[0] = r;   // never true; keeps the loop alive
+}
+
+// dst[i] = src[i] for n 16-byte pieces, 4 pieces in flight per thread
+__global__ void __launch_bounds__(256) plain_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) if (base + 256 * i < n) v[i] = src[base + 256 * i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) if (base + 256 * i < n) dst[base + 256 * i] = v[i];
+}
+
+}  // namespace glm
+
+using namespace glm;
+
+extern "C" {
+
+int glm_bench_mfma(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_stream) {
+    if (!sink_dev) return GLM_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0) return GLM_ERR_GEOM;
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink_dev, iters);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+int glm_bench_copy(const void *src_dev, void *dst_dev, size_t bytes, void *hip_stream) {
+    if (!src_dev || !dst_dev) return GLM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(src_dev) | reinterpret_cast<uintptr_t>(dst_dev) | bytes) & 15u) return GLM_ERR_ALIGN;
+    if (bytes == 0) return GLM_OK;
+    const int64_t n = (int64_t)(bytes / 16);
+    const int64_t grid = (n + 1023) / 1024;
+    if (grid > INT32_MAX) return GLM_ERR_GEOM;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const u32x4 *)src_dev, (u32x4 *)dst_dev, n);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+}  // extern "C"
