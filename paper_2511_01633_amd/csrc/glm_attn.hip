@@ -75,6 +75,7 @@ __device__ __forceinline__ int wave_max(int v) {
 // keys): with thousands of keys the rounding of single weights averages out far below the
 // error bound, and this kernel is MFMA bound there.
 constexpr int kSplitLimit = 1024;
+constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format, no swizzle
 
 template <int D>
 __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
@@ -93,6 +94,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     __shared__ int wave_lim[4], wave_min[4];
 
     const int tid = threadIdx.x;
+    __builtin_assume(tid >= 0 && tid < 256);
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int n32 = lane & 31;                 // row within the wave's 32 rows / token within a tile
@@ -193,16 +195,28 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         return (int64_t)min(max(id, 0), a.num_blocks - 1);
     };
 
+    // Global loads go through buffer descriptors: one descriptor per block (base = the block, range =
+    // its bytes, built with scalar instructions), and per thread a fixed 32-bit byte offset for each
+    // of its PPT 16-byte pieces of a tile - no per-load 64-bit vector address arithmetic.
     u32x4 stage[PPT];
-    auto issue_loads = [&](int64_t idA, int64_t idB) {
+    int piece_off[PPT];
+    bool piece_b[PPT];
 #pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int gp = tid + 256 * i;
-            const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
-            const int64_t id = (p / BLOCK_PIECES) ? idB : idA;
-            const __bf16 *src = a.pool + id * blk_elems + ((int64_t)plane * a.Hkv + kvh) * slab + (p % BLOCK_PIECES) * 8;
-            stage[i] = *reinterpret_cast<const u32x4 *>(src);
-        }
+    for (int i = 0; i < PPT; ++i) {
+        const int gp = tid + 256 * i;
+        const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
+        piece_b[i] = (p / BLOCK_PIECES) != 0;
+        piece_off[i] = (((plane * a.Hkv + kvh) * (int)slab) + (p % BLOCK_PIECES) * 8) * 2;
+    }
+    const int blk_bytes = (int)(blk_elems * 2);
+    auto issue_loads = [&](int64_t idA, int64_t idB) {
+        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(a.pool + idA * blk_elems), 0, blk_bytes, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(a.pool + idB * blk_elems), 0, blk_bytes, kBufferFlags);
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+            stage[i] = __builtin_amdgcn_raw_buffer_load_b128(piece_b[i] ? rb : ra, piece_off[i], 0, 0);
     };
     auto write_stage = [&](int buf, int t, bool maybe_tail) {
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
