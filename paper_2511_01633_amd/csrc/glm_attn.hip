@@ -280,13 +280,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         constexpr bool FAST = decltype(fast_tag)::value;
         constexpr bool SPLIT = decltype(split_tag)::value;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
-        if (FAST || t + 2 < ntiles) {
-            write_stage(buf_t2, t + 2, !FAST);
-            if (FAST || t + 3 < ntiles) {
-                issue_loads(idA_next, idB_next);
-                if (FAST || t + 4 < ntiles) { idA_next = phys(c.b0 + 2 * t + 8); idB_next = phys(c.b0 + 2 * t + 9); }
-            }
-        }
         // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]; raw scores,
         // the factor scale*log2(e) (> 0) is folded into the exponent
         if (!FAST && pos0 + T > lim_eff) {
@@ -297,7 +290,15 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         float m_tile = sT[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32)) * a.scale_log2;
+        const float m_other = __shfl_xor(m_tile, 32);      // in flight while the next tile is staged below
+        if (FAST || t + 2 < ntiles) {
+            write_stage(buf_t2, t + 2, !FAST);
+            if (FAST || t + 3 < ntiles) {
+                issue_loads(idA_next, idB_next);
+                if (FAST || t + 4 < ntiles) { idA_next = phys(c.b0 + 2 * t + 8); idB_next = phys(c.b0 + 2 * t + 9); }
+            }
+        }
+        m_tile = fmaxf(m_tile, m_other) * a.scale_log2;
         const float m_new = fmaxf(m_run, m_tile);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         if (__any(m_new > m_run)) {
