@@ -202,17 +202,27 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     // K/V tile); the rest is cut into wave-private items of 16 rows.
     const int coop_min_rows = env_int("GLM_PLAN_COOP_MIN_ROWS", 128);
     auto is_coop = [&](int64_t rows) { return rows >= coop_min_rows; };
-    // chunk length: enough work items to fill every SIMD a few times over, yet several tiles each
-    int64_t units = 0;
+    // Chunk length, separately for the two launches.  Wave-private items: as many items as the chip has
+    // wave slots (2 per SIMD), so that the launch is one balanced round; at least 4 tiles each.
+    // Cooperative workgroups are MFMA bound and each chunk costs every member a partial result, so they
+    // are cut only as far as filling the chip's workgroup slots (2 per CU) one and a half times requires
+    // (measured on the 70B-shaped tree: fewer, longer chunks leave a ragged last round).
+    int64_t units = 0, units_coop = 0;
     for (auto &s : segs) {
         const int64_t rows = (int64_t)s.members.size() * G;
-        units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, is_coop(rows) ? kCoopRows : kRowsPerWave);
+        if (is_coop(rows)) units_coop += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kCoopRows);
+        else units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kRowsPerWave);
     }
     const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 8);
     int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
     cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
     cb = (cb + 1) & ~1;   // whole 32-token tiles
     if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb = std::max(1, forced);
+    const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 3);
+    int32_t cb_coop = (int32_t)std::max<int64_t>(32, units_coop * p.g.num_kv_heads / std::max(1, target_coop));
+    cb_coop = (cb_coop + 1) & ~1;
+    if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
+    auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : cb; };
 
     std::vector<std::vector<int32_t>> per_req(B);
     std::vector<Work> coop;
@@ -226,7 +236,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     std::vector<int32_t> n_chunks_of(B, 0);
     for (auto &s : segs) {
         const int32_t len = s.b1 - s.b0;
-        const int32_t nc = ceil_div(len, cb);
+        const int32_t nc = ceil_div(len, chunk_blocks((int64_t)s.members.size() * G));
         for (int32_t r : s.members) n_chunks_of[r] += nc;
     }
     for (auto &s : segs) {
@@ -239,7 +249,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         const int waves = cooperative ? kBigWaves : 1;
         const int32_t tile_rows = cooperative ? kCoopRows : kRowsPerWave;
         const int32_t len = s.b1 - s.b0;
-        const int32_t nc = ceil_div(len, cb);
+        const int32_t nc = ceil_div(len, chunk_blocks(rows));
         // spread the blocks evenly over the nc chunks, in whole tiles of 2 blocks
         int32_t per_chunk = ceil_div(len, nc);
         per_chunk = (per_chunk + 1) & ~1;
