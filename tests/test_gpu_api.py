@@ -1,0 +1,142 @@
+"""GPU tests of the boundary itself: debug validation (GLM_VALIDATE=1), workspace handling,
+long sequences, reruns, and the reference kernels."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _gu():
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture
+def validate_env():
+    old = os.environ.get("GLM_VALIDATE")
+    os.environ["GLM_VALIDATE"] = "1"
+    yield
+    if old is None:
+        del os.environ["GLM_VALIDATE"]
+    else:
+        os.environ["GLM_VALIDATE"] = old
+
+
+def test_validate_rejects_bad_tables_and_lengths(validate_env):
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(5000, prefix_groups=[[0, 1]], prefix_tokens=[32], suffix_tokens=[3, 9, 20], num_q_heads=8,
+                        num_kv_heads=2, head_dim=128)
+    dw = gu.DeviceWorkload(w)
+    ws = torch.empty(glm.glm_attn_workspace_bytes(w.geom, w.B, 0, w.max_blocks * 16), dtype=torch.uint8, device="cuda")
+
+    def call(tables, lens):
+        return glm.glm_attn_decode(w.geom, dw.pool, dw.q, dw.out, tables, w.max_blocks, lens, w.B, w.scale, None, ws,
+                                   check=False)
+    assert call(dw.tables, dw.seq_lens) == glm.GLM_OK
+    bad = w.block_tables.copy(); bad[1, 0] = w.geom.num_blocks          # id past the pool
+    assert call(gu.dev(bad), dw.seq_lens) == glm.GLM_ERR_RANGE
+    bad = w.block_tables.copy(); bad[0, 1] = -1                         # hole inside the live range
+    assert call(gu.dev(bad), dw.seq_lens) == glm.GLM_ERR_RANGE
+    lens = w.seq_lens.copy(); lens[2] = w.max_blocks * 16 + 1           # longer than the table can hold
+    assert call(dw.tables, gu.dev(lens)) == glm.GLM_ERR_RANGE
+    torch.cuda.synchronize()
+    # prefill: q_len > seq_len, cu_q_lens not ending at sum_q
+    wp = W.custom_prefill(5001, prefix_groups=[], prefix_tokens=[], q_lens=[4, 7], num_q_heads=4, num_kv_heads=2,
+                          head_dim=64)
+    dp = gu.DeviceWorkload(wp)
+
+    def pcall(lens, cu, sum_q):
+        return glm.glm_attn_prefill_on_prefix(wp.geom, dp.pool, dp.q, dp.out, dp.tables, wp.max_blocks, lens, cu, wp.B,
+                                              sum_q, 7, wp.scale, None, None, check=False)
+    assert pcall(dp.seq_lens, dp.cu, wp.sum_q) == glm.GLM_OK
+    assert pcall(gu.dev(np.array([3, 7], np.int32)), dp.cu, wp.sum_q) == glm.GLM_ERR_RANGE
+    assert pcall(dp.seq_lens, dp.cu, wp.sum_q + 1) == glm.GLM_ERR_RANGE
+    torch.cuda.synchronize()
+
+
+def test_validate_rejects_bad_copy_lists(validate_env):
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    geom = W.Geometry(32, 16, 2, 2, 64)
+    pool = gu.dev(np.zeros((32, 2, 2, 16, 64), np.uint16))
+    i32 = lambda *v: gu.dev(np.array(v, np.int32))
+    fork = lambda s, d, n: glm.glm_kv_fork_copy(geom, pool, s, d, n, 2, check=False)
+    assert fork(i32(1, 2), i32(3, 4), i32(5, 16)) == glm.GLM_OK
+    assert fork(i32(1, 2), i32(3, 3), i32(5, 16)) == glm.GLM_ERR_RANGE      # duplicate destination
+    assert fork(i32(1, 2), i32(2, 4), i32(5, 16)) == glm.GLM_ERR_RANGE      # destination is also a source
+    assert fork(i32(1, 32), i32(3, 4), i32(5, 16)) == glm.GLM_ERR_RANGE     # source outside the pool
+    assert fork(i32(1, 2), i32(3, 4), i32(5, 17)) == glm.GLM_ERR_RANGE      # more rows than a block has
+    other = gu.dev(np.zeros((8, 2, 2, 16, 64), np.uint16))
+    assert glm.glm_kv_gather(geom, pool, i32(1, 2), other, i32(0, 0), 2, check=False) == glm.GLM_ERR_RANGE
+    assert glm.glm_kv_gather(geom, pool, i32(1, -2), other, None, 2, check=False) == glm.GLM_ERR_RANGE
+    assert glm.glm_kv_gather(geom, pool, i32(1, 2), other, i32(0, 7), 2, check=False) == glm.GLM_OK
+    torch.cuda.synchronize()
+
+
+def test_workspace_sizes():
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(5100, prefix_groups=[[0, 1, 2]], prefix_tokens=[64], suffix_tokens=[700, 33, 260, 90],
+                        num_q_heads=16, num_kv_heads=4, head_dim=128)
+    ref = oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    small = torch.empty(max(16, plan.workspace_bytes - 16), dtype=torch.uint8, device="cuda")
+    st = glm.glm_attn_decode(w.geom, dw.pool, dw.q, dw.out, dw.tables, w.max_blocks, dw.seq_lens, w.B, w.scale, plan,
+                             small, check=False)
+    assert st == glm.GLM_ERR_WORKSPACE
+    # without a plan the number of splits follows the workspace: the smallest legal one gives one split
+    one = torch.empty(glm.glm_attn_workspace_bytes(w.geom, w.B, 0, 1), dtype=torch.uint8, device="cuda")
+    got1 = dw.decode(plan=None, workspace=one)
+    big = torch.empty(glm.glm_attn_workspace_bytes(w.geom, w.B, 0, w.max_blocks * 16), dtype=torch.uint8, device="cuda")
+    gotn = dw.decode(plan=None, workspace=big)
+    assert np.abs(got1 - ref).max() <= gu.TOL and np.abs(gotn - ref).max() <= gu.TOL
+    assert np.abs(got1 - gotn).max() <= 1e-5           # the number of splits does not matter
+
+
+def test_long_sequence_and_bit_identical_reruns():
+    gu = _gu()
+    w = W.custom_decode(5200, prefix_groups=[], prefix_tokens=[], suffix_tokens=[32767, 5], num_q_heads=8, num_kv_heads=2,
+                        head_dim=128)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    got = dw.decode(plan=plan)
+    sel_r = np.array([0, 0, 1, 0], np.int32); sel_h = np.array([0, 7, 3, 4], np.int32)
+    ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, sel_r, sel_h)
+    assert np.abs(got[sel_r, sel_h] - ref).max() <= gu.TOL
+    np.testing.assert_array_equal(dw.decode(plan=plan), got)
+    got_np = dw.decode(plan=None)
+    assert np.abs(got_np - got).max() <= 1e-5
+    wp = W.custom_prefill(5201, prefix_groups=[[0, 1]], prefix_tokens=[1504], q_lens=[200, 77], num_q_heads=8,
+                          num_kv_heads=2, head_dim=64)
+    dp = gu.DeviceWorkload(wp)
+    a = dp.prefill(plan=None)
+    np.testing.assert_array_equal(dp.prefill(plan=None), a)
+    refp = oracle.attention(wp.geom, wp.pool, wp.q, wp.block_tables, wp.seq_lens, wp.scale, cu_q_lens=wp.cu_q_lens)
+    assert np.abs(a - refp).max() <= gu.TOL
+
+
+def test_reference_kernels():
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    glm.glm_bench_copy(src, dst, src.numel() * 4)
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    glm.glm_bench_mfma(sink, 64, 10)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst) and float(sink.abs().sum()) == 0.0
+    glm.glm_profile_reset()
+    glm.glm_profile_enable(True)
+    glm.glm_kv_gather(W.Geometry(4, 16, 1, 1, 64), src, None, dst, None, 4)
+    glm.glm_profile_enable(False)
+    ms, n = glm.glm_profile_read(glm.KERNEL_IDS["kv_gather"])
+    glm.glm_profile_reset()
+    assert n == 1 and ms > 0
