@@ -6,6 +6,7 @@
 // for decode items of at most 16 rows.  Everything is computed transposed so that a query row
 // lives in one lane column; S^T comes out of the QK^T MFMA in exactly the register layout the
 // PV MFMA wants P^T in, and V^T is produced by the LDS transpose read (ds_read_b64_tr_b16).
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <type_traits>
@@ -39,6 +40,7 @@ struct AttnArgs {
     int32_t max_blocks, B, Hkv, Hq, G, num_blocks;
     int32_t mode;
     int32_t n_split, chunk_blocks, row_tiles;   // implicit modes
+    int32_t items_per_xcd;      // planned prefill: work items per XCD (list length / 8)
     float scale_log2;           // scale * log2(e)
 };
 
@@ -105,10 +107,16 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     int kvh;
     const int G = a.G;
     if (a.mode == kPlanned) {
+        // workgroup L runs on XCD L % 8 and takes the (L / 8)-th (work item, kv head) pair of that XCD's
+        // list.  Decode: kv head fastest (row tiles of one chunk are neighbours in the list and meet in
+        // L2).  Prefill: kv head slowest, so that the workgroups in flight on an XCD are the row tiles of
+        // few (request, kv head) streams and each stream's K/V is pulled into that L2 once.
         const int L = blockIdx.x;
         const int x = L % kXcds, k = L / kXcds;
-        kvh = k % a.Hkv;
-        const glm_chunk *cp = a.chunks + ((k / a.Hkv) * kXcds + x);
+        int ci;
+        if (a.cu_q_lens) { kvh = k / a.items_per_xcd; ci = k % a.items_per_xcd; }
+        else { kvh = k % a.Hkv; ci = k / a.Hkv; }
+        const glm_chunk *cp = a.chunks + (ci * kXcds + x);
         c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
         c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
         c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
@@ -117,11 +125,17 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         c.row0 = __builtin_amdgcn_readfirstlane(cp->row0);
         c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
         if (c.n_mem == 0) return;
-    } else {                                   // prefill without a plan: request x row tile x kv head
-        int L = blockIdx.x;
-        kvh = L % a.Hkv; L /= a.Hkv;
-        const int t = L % a.row_tiles;
-        const int r = L / a.row_tiles;
+    } else {
+        // prefill without a plan: XCD x takes the requests x, x+8, ..; on it kv head is the slowest
+        // index, then the request, then the row tile (same reason as above)
+        const int L = blockIdx.x;
+        const int x = L % kXcds;
+        int k = L / kXcds;
+        const int t = k % a.row_tiles; k /= a.row_tiles;
+        const int per_xcd = (a.B + kXcds - 1) / kXcds;
+        const int r = x + kXcds * (k % per_xcd);
+        kvh = k / per_xcd;
+        if (r >= a.B) return;
         c.rep = r;
         c.b0 = 0;
         c.b1 = INT32_MAX;
@@ -974,12 +988,13 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
     if (plan) {
         a.mode = kPlanned;
         a.chunks = plan->d.chunks[1];
+        a.items_per_xcd = std::max(1, plan->d.n_chunks[1] / kXcds);
         e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
     } else {
         if (max_q_len == 0) return GLM_OK;
         a.mode = kImplicitPrefill;
         const int64_t tiles = ((int64_t)max_q_len * G + kCoopRows - 1) / kCoopRows;
-        const int64_t grid = tiles * B * Hkv;
+        const int64_t grid = tiles * (((int64_t)B + kXcds - 1) / kXcds) * kXcds * Hkv;
         if (grid > INT32_MAX) return GLM_ERR_GEOM;
         a.row_tiles = (int32_t)tiles;
         e = launch_coop(D, a, grid, st);
