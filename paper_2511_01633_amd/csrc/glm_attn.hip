@@ -49,7 +49,8 @@ struct MergeArgs {
     const float *part_acc;
     float *out;
     const int32_t *seq_lens;
-    const int32_t *merge_off, *merge_slots, *merge_kind;   // nullptr: implicit
+    const int32_t *merge_slots, *merge_kind, *merge_cnt;   // nullptr: implicit
+    int32_t merge_stride;
     int32_t Hq, max_blocks, n_split, chunk_blocks;
 };
 
@@ -717,34 +718,52 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
     int n, first = 0;
     const int32_t *slots = nullptr;
     if (a.merge_kind) {
+        // the slot list sits at a fixed stride, so its fetch does not wait for the count
+        slots = a.merge_slots + (int64_t)r * a.merge_stride;
+        const int first_slot = lane < a.merge_stride ? slots[lane] : 0;
         const int kind = a.merge_kind[r];
+        n = a.merge_cnt[r];
         if (kind == kMergeDirect) return;
         if (kind == kMergeZero) {
 #pragma unroll
             for (int e = 0; e < E; ++e) dst[e] = 0.f;
             return;
         }
-        slots = a.merge_slots + a.merge_off[r];
-        n = a.merge_off[r + 1] - a.merge_off[r];
+        first = first_slot;   // lane's slot of the first group of 64
     } else {
         const int nb = min((a.seq_lens[r] + kBlockSize - 1) / kBlockSize, a.max_blocks);
         n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
-        first = r * a.n_split;
+        first = r * a.n_split + lane;
     }
     float M = -INFINITY, l = 0.f, o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
-    // 64 partials at a time: lane i fetches (m, l) of partial i, so the fetches overlap; the
-    // running maximum M carries over between groups and the order of accumulation is fixed
+    // 64 partials at a time: lane i fetches (m, l) of partial i, so the fetches overlap; the first
+    // accumulator rows are requested before the (m, l) values are needed.  The running maximum M
+    // carries over between groups and the order of accumulation is fixed.
     for (int base = 0; base < n; base += 64) {
         const int cnt = min(64, n - base);
         int64_t my_slot = 0;
         float my_m = -INFINITY, my_l = 0.f;
         if (lane < cnt) {
-            my_slot = ((int64_t)(slots ? slots[base + lane] : first + base + lane)) * a.Hq + h;
+            const int sl = base == 0 ? first : (slots ? slots[base + lane] : r * a.n_split + base + lane);
+            my_slot = (int64_t)sl * a.Hq + h;
             my_m = a.part_ml[my_slot * 2];
             my_l = a.part_ml[my_slot * 2 + 1];
         }
+        const int lo32 = (int)(my_slot & 0xffffffff), hi32 = (int)(my_slot >> 32);
+        auto fetch = [&](int i0, float (&v)[8][E]) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = min(i0 + j, cnt - 1);
+                const int64_t s = ((int64_t)__shfl(hi32, i) << 32) | (uint32_t)__shfl(lo32, i);
+                const float *src = a.part_acc + s * D + lane * E;
+#pragma unroll
+                for (int e = 0; e < E; ++e) v[j][e] = src[e];
+            }
+        };
+        float v[8][E];
+        fetch(0, v);
         float gm = my_m;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off));
@@ -760,22 +779,14 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
         l += lw;
-        const int lo32 = (int)(my_slot & 0xffffffff), hi32 = (int)(my_slot >> 32);
         for (int i0 = 0; i0 < cnt; i0 += 8) {               // 8 independent fetches in flight at a time
-            float v[8][E], w[8];
+            if (i0 > 0) fetch(i0, v);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int i = min(i0 + j, cnt - 1);
-                const int64_t s = ((int64_t)__shfl(hi32, i) << 32) | (uint32_t)__shfl(lo32, i);
-                w[j] = (i0 + j < cnt) ? __shfl(my_w, i) : 0.f;
-                const float *src = a.part_acc + s * D + lane * E;
+                const float w = (i0 + j < cnt) ? __shfl(my_w, min(i0 + j, cnt - 1)) : 0.f;
 #pragma unroll
-                for (int e = 0; e < E; ++e) v[j][e] = src[e];
+                for (int e = 0; e < E; ++e) o[e] += (i0 + j < cnt) ? v[j][e] * w : 0.f;
             }
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] += (i0 + j < cnt) ? v[j][e] * w[j] : 0.f;
         }
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
@@ -939,9 +950,10 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
             a.chunks = plan->d.chunks[0];
             e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
         }
-        m.merge_off = plan->d.merge_off;
         m.merge_slots = plan->d.merge_slots;
         m.merge_kind = plan->d.merge_kind;
+        m.merge_cnt = plan->d.merge_cnt;
+        m.merge_stride = plan->merge_stride;
     } else {
         a.mode = kImplicitDecode;
         a.row_tiles = (G + kRowsPerWave - 1) / kRowsPerWave;

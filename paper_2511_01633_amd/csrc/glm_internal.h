@@ -25,8 +25,9 @@ struct DevicePlan {                   // pointers into the plan's single device 
     int32_t n_chunks[2] = {0, 0};     // multiples of kXcds (padded with n_mem == 0 entries)
     const int32_t *members = nullptr;
     const int32_t *block_ids = nullptr;   // physical ids of every planned run, see glm_chunk::ids_off
-    const int32_t *merge_off = nullptr;   // [B+1]
-    const int32_t *merge_slots = nullptr; // member-slot indices, request by request
+    const int32_t *merge_off = nullptr;   // [B+1], = r * merge_stride
+    const int32_t *merge_slots = nullptr; // member-slot indices, merge_stride per request
+    const int32_t *merge_cnt = nullptr;   // [B] partials of each request
     const int32_t *merge_kind = nullptr;  // [B]
 };
 
@@ -58,7 +59,8 @@ struct glm_plan {
     int32_t B = 0, max_blocks = 0;
     int32_t kind = glm::kDecode;
     std::vector<glm_chunk> chunks[2];
-    std::vector<int32_t> members, block_ids, merge_off, merge_slots, merge_kind;
+    std::vector<int32_t> members, block_ids, merge_off, merge_slots, merge_kind, merge_cnt;
+    int32_t merge_stride = 1;
     int32_t n_slots = 0;              // member slots; a slot holds Hq partial rows
     int32_t n_shared_segments = 0;
     int64_t shared_blocks = 0;

@@ -202,8 +202,9 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     // K/V tile); the rest is cut into wave-private items of 16 rows.
     const int coop_min_rows = env_int("GLM_PLAN_COOP_MIN_ROWS", 128);
     auto is_coop = [&](int64_t rows) { return rows >= coop_min_rows; };
-    // Chunk length, separately for the two launches.  Wave-private items: as many items as the chip has
-    // wave slots (2 per SIMD), so that the launch is one balanced round; at least 4 tiles each.
+    // Chunk length, separately for the two launches.  Wave-private items: a little fewer items than the
+    // chip has wave slots (2 per SIMD = 2048), so that the launch, padding included, is one round; at
+    // least 4 tiles each.
     // Cooperative workgroups are MFMA bound and each chunk costs every member a partial result, so they
     // are cut only as far as filling the chip's workgroup slots (2 per CU) one and a half times requires
     // (measured on the 70B-shaped tree: fewer, longer chunks leave a ragged last round).
@@ -213,7 +214,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
         if (is_coop(rows)) units_coop += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kCoopRows);
         else units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kRowsPerWave);
     }
-    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 8);
+    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 7);
     int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
     cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
     cb = (cb + 1) & ~1;   // whole 32-token tiles
@@ -298,16 +299,23 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
             if (last) break;
         }
     }
+    // merge lists with a fixed stride per request, so that a merging wave can fetch its slot list and
+    // its count in parallel (merge_off[r] = r * stride is kept for inspection)
+    size_t stride = 1;
+    for (int32_t r = 0; r < B; ++r) stride = std::max(stride, per_req[r].size());
+    p.merge_stride = (int32_t)stride;
     p.merge_off.assign(B + 1, 0);
+    p.merge_cnt.assign(B, 0);
     p.merge_kind.assign(B, kMergeList);
-    p.merge_slots.clear();
+    p.merge_slots.assign((size_t)B * stride, 0);
     for (int32_t r = 0; r < B; ++r) {
-        p.merge_off[r] = (int32_t)p.merge_slots.size();
+        p.merge_off[r] = (int32_t)(r * stride);
+        p.merge_cnt[r] = (int32_t)per_req[r].size();
         if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
         else if (per_req[r].empty()) p.merge_kind[r] = kMergeDirect;
-        p.merge_slots.insert(p.merge_slots.end(), per_req[r].begin(), per_req[r].end());
+        std::copy(per_req[r].begin(), per_req[r].end(), p.merge_slots.begin() + (size_t)r * stride);
     }
-    p.merge_off[B] = (int32_t)p.merge_slots.size();
+    p.merge_off[B] = (int32_t)((size_t)B * stride);
     std::vector<Work> quads = pack_quads(families, singles);
     p.chunks[0] = deal_to_xcds(quads, 4);
     p.chunks[1] = deal_to_xcds(coop, 1);
@@ -349,6 +357,8 @@ int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
     p.members.clear();
     p.merge_off.assign(B + 1, 0);
     p.merge_slots.clear();
+    p.merge_cnt.assign(B, 0);
+    p.merge_stride = 1;
     p.merge_kind.assign(B, kMergeDirect);
     p.n_slots = 0;
     return GLM_OK;
@@ -423,6 +433,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
             const size_t o_off = append(buf, p->merge_off);
             const size_t o_slots = append(buf, p->merge_slots);
             const size_t o_kind = append(buf, p->merge_kind);
+            const size_t o_cnt = append(buf, p->merge_cnt);
             hipError_t e = hipGetDevice(&p->device);
             if (e == hipSuccess) e = hipMalloc(&p->dev, buf.size());
             if (e == hipSuccess)
@@ -443,6 +454,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
                 p->d.merge_off = (const int32_t *)(d + o_off);
                 p->d.merge_slots = (const int32_t *)(d + o_slots);
                 p->d.merge_kind = (const int32_t *)(d + o_kind);
+                p->d.merge_cnt = (const int32_t *)(d + o_cnt);
             }
         } catch (...) {
             st = GLM_ERR_ALLOC;
