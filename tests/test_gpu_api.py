@@ -140,3 +140,53 @@ def test_reference_kernels():
     ms, n = glm.glm_profile_read(glm.KERNEL_IDS["kv_gather"])
     glm.glm_profile_reset()
     assert n == 1 and ms > 0
+
+
+def test_blocks_beyond_4_gib_of_pool():
+    """Block offsets need 64 bits: the same small workloads, with their live blocks moved to the top of a
+    5 GiB pool (only the live blocks are initialised; nothing else may be read)."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    big_blocks = 5 * (1 << 30) // (2 * 8 * 16 * 128 * 2)            # 64 KiB blocks
+    w = W.custom_decode(5300, prefix_groups=[[0, 1, 2, 3]], prefix_tokens=[96], suffix_tokens=[40, 3, 300, 77, 12],
+                        num_q_heads=32, num_kv_heads=8, head_dim=128)
+    wp = W.custom_prefill(5301, prefix_groups=[[0, 1]], prefix_tokens=[160], q_lens=[70, 33], num_q_heads=32,
+                          num_kv_heads=8, head_dim=128)
+    pool = torch.empty((big_blocks,) + w.pool.shape[1:], dtype=torch.int16, device="cuda")
+    for wl, is_prefill in ((w, False), (wp, True)):
+        off = big_blocks - wl.geom.num_blocks
+        assert off * 65536 > (1 << 32)
+        live = wl.live_block_ids()
+        pool[torch.from_numpy(live + off).cuda()] = gu.dev(wl.pool[live])
+        geom = W.Geometry(big_blocks, 16, 8, 32, 128)
+        tables = np.where(wl.block_tables >= 0, wl.block_tables + off, -1).astype(np.int32)
+        ref = oracle.attention(wl.geom, wl.pool, wl.q, wl.block_tables, wl.seq_lens, wl.scale, cu_q_lens=wl.cu_q_lens)
+        out = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+        q, t_dev, lens = gu.dev(wl.q), gu.dev(tables), gu.dev(wl.seq_lens)
+        if not is_prefill:
+            for use_plan in (False, True):
+                plan = glm.glm_plan_create(geom, tables, wl.max_blocks, wl.seq_lens, None, wl.B) if use_plan else None
+                nbytes = plan.workspace_bytes if plan else glm.glm_attn_workspace_bytes(geom, wl.B, 0, wl.max_blocks * 16)
+                ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                out.fill_(float("nan"))
+                glm.glm_attn_decode(geom, pool, q, out, t_dev, wl.max_blocks, lens, wl.B, wl.scale, plan, ws)
+                torch.cuda.synchronize()
+                assert np.abs(out.cpu().numpy() - ref).max() <= gu.TOL
+        else:
+            glm.glm_attn_prefill_on_prefix(geom, pool, q, out, t_dev, wl.max_blocks, lens, gu.dev(wl.cu_q_lens), wl.B,
+                                           wl.sum_q, int(wl.q_lens.max()), wl.scale, None, None)
+            torch.cuda.synchronize()
+            assert np.abs(out.cpu().numpy() - ref).max() <= gu.TOL
+    # copies at high offsets: fork inside the big pool, gather from its top into a small buffer
+    off = big_blocks - 8
+    src = gu.dev(np.array([off + 1, off + 2], np.int32)); dst = gu.dev(np.array([off + 5, off + 6], np.int32))
+    before = gu.host_u16(pool[off:off + 8])
+    glm.glm_kv_fork_copy(W.Geometry(big_blocks, 16, 8, 32, 128), pool, src, dst, gu.dev(np.array([16, 5], np.int32)), 2)
+    staged = torch.zeros((2,) + tuple(pool.shape[1:]), dtype=torch.int16, device="cuda")
+    glm.glm_kv_gather(W.Geometry(big_blocks, 16, 8, 32, 128), pool, dst, staged, None, 2)
+    torch.cuda.synchronize()
+    exp = before.copy()
+    exp[5] = before[1]
+    exp[6, :, :, :5] = before[2, :, :, :5]
+    np.testing.assert_array_equal(gu.host_u16(pool[off:off + 8]), exp)
+    np.testing.assert_array_equal(gu.host_u16(staged), exp[5:7])
