@@ -159,8 +159,20 @@ def bench_prefill(glm, w, steps, warmup):
     kt = _kernel_times(glm, step, min(steps, 16))
     tf = w.flops() / ms / 1e9
     ktf = w.flops() / kt["attn_stream_w4"]["avg_us"] / 1e6
+    # the append of the same new tokens' K/V (what precedes this attention call in a layer), timed on its own
+    import workloads as W
+    slots = _dev(W.new_token_slots(w))
+    k_new = torch.randint(-30000, 30000, (w.sum_q, g.num_kv_heads, g.head_dim), dtype=torch.int16, device="cuda")
+    v_new = torch.randint(-30000, 30000, (w.sum_q, g.num_kv_heads, g.head_dim), dtype=torch.int16, device="cuda")
+
+    def app(i):
+        glm.glm_kv_append(g, pool, k_new, v_new, slots, w.sum_q, None)
+
+    ams = _time_steps(app, steps, warmup)
+    abytes = 2 * (k_new.numel() + v_new.numel()) * 2 + slots.numel() * 8          # rows read + rows written + slots
     return {"workload": w.name, "ms_per_step": ms, "flops": w.flops(), "TFLOPs": tf,
             "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "kernels": kt,
+            "kv_append": {"tokens": int(w.sum_q), "ms": ams, "bytes": abytes, "GBps": abytes / ams / 1e6},
             "roofline": {"kernel": "attn_stream_w4", "bound": "mfma", "achieved": ktf, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": ktf / MFMA_BF16_PEAK_TFLOPS, "traffic": _traffic("attn_stream_w4", w.name)}}
 

@@ -136,6 +136,19 @@ GLM_API int glm_kv_gather(glm_geom g, const void *src_base_dev, const int32_t *s
                   const int32_t *dst_ids_dev, int32_t n, void *hip_stream);
 
 /*
+ * K/V append (paper Sec. 2.4: prefill fills the cache with the K and V of the input, decoding extends
+ * it by one token per step).  Token i of the batch has K and V rows k_new[i], v_new[i] of shape
+ * [Hkv][d] bf16; they are written to token slot slot_mapping[i] = block_id * block_size + offset of the
+ * pool (both planes, every kv head).  A negative slot skips the token (padding).  All other bytes of
+ * the pool are left unchanged.  Preconditions (GLM_VALIDATE=1 -> GLM_ERR_RANGE): slots below
+ * num_blocks * block_size and distinct.  n_tokens == 0 returns GLM_OK without a launch.
+ *   k_new_dev, v_new_dev   bf16 [n_tokens][Hkv][d], 16-byte aligned
+ *   slot_mapping_dev       int64 [n_tokens]
+ */
+GLM_API int glm_kv_append(glm_geom g, void *kv_pool_dev, const void *k_new_dev, const void *v_new_dev,
+                          const int64_t *slot_mapping_dev, int32_t n_tokens, void *hip_stream);
+
+/*
  * Plan: derived on the host from the block tables.  Maximal runs of logical blocks that the
  * same set of requests reference through identical physical ids become shared segments
  * (a prefix tree: agent template -> graph context -> private suffix, paper Sec. 5.2); the plan
@@ -186,8 +199,8 @@ GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing H
  * Optional per-kernel timing for benchmarks.  While enabled, every kernel the library launches
  * is bracketed by two HIP events recorded on the stream it is launched on.  glm_profile_read
  * waits for the recorded events of one kernel kind and returns their summed duration and count
- * since the last glm_profile_reset.  Kernel ids: 0 streaming attention kernel with 1-wave
- * workgroups, 1 the same with 4-wave workgroups, 2 split-K merge, 3 gather, 4 fork copy.
+ * since the last glm_profile_reset.  Kernel ids: 0 wave-private streaming attention kernel,
+ * 1 cooperative attention kernel, 2 split-K merge, 3 gather, 4 fork copy, 5 K/V append.
  * Disabled by default; enabling it adds event records between kernels, so whole-call timings
  * should be taken with it off.
  */

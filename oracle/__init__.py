@@ -9,5 +9,6 @@ from .loader import (  # noqa: F401
     attention_weights,
     fork_copy,
     gather,
+    kv_append,
     lib_path,
 )

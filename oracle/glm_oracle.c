@@ -234,3 +234,23 @@ int glm_oracle_gather(oracle_geom g, const uint16_t *src_base, const int32_t *sr
     }
     return 0;
 }
+
+/* K/V append (the cache is filled by prefill and extended by each decode step, Sec. 2.4): token i's K and
+ * V rows [Hkv][d] go to token slot slots[i] = block * block_size + offset; negative slots are skipped. */
+int glm_oracle_kv_append(oracle_geom g, uint16_t *pool, const uint16_t *k_new, const uint16_t *v_new,
+                         const int64_t *slots, int32_t n_tokens) {
+    if (check_geom(&g)) return -1;
+    const int64_t d = g.head_dim, bs = g.block_size, Hkv = g.num_kv_heads;
+    for (int i = 0; i < n_tokens; ++i) {
+        const int64_t slot = slots[i];
+        if (slot < 0) continue;
+        if (slot >= (int64_t)g.num_blocks * bs) return -2;
+        const int64_t blk = slot / bs, t = slot % bs;
+        for (int h = 0; h < Hkv; ++h)
+            for (int c = 0; c < d; ++c) {
+                pool[((((blk * 2 + 0) * Hkv + h) * bs + t) * d) + c] = k_new[((int64_t)i * Hkv + h) * d + c];
+                pool[((((blk * 2 + 1) * Hkv + h) * bs + t) * d) + c] = v_new[((int64_t)i * Hkv + h) * d + c];
+            }
+    }
+    return 0;
+}

@@ -127,3 +127,14 @@ def gather(geom, src, src_ids, dst, dst_ids, n: Optional[int] = None) -> None:
                                    _p(t, np.int32), ctypes.c_int32(n))
     if st:
         raise RuntimeError("oracle gather failed: %d" % st)
+
+
+def kv_append(geom, pool, k_new, v_new, slots) -> None:
+    """In place on `pool`: token i's rows k_new[i], v_new[i] ([Hkv, d] uint16) go to token slot slots[i]."""
+    sl = np.ascontiguousarray(slots, dtype=np.int64)
+    k_new = np.ascontiguousarray(k_new); v_new = np.ascontiguousarray(v_new)
+    assert pool.dtype == np.uint16 and pool.flags["C_CONTIGUOUS"]
+    st = _load().glm_oracle_kv_append(_geom(geom), _p(pool, np.uint16), _p(k_new, np.uint16), _p(v_new, np.uint16),
+                                      sl.ctypes.data_as(ctypes.c_void_p), ctypes.c_int32(sl.shape[0]))
+    if st:
+        raise RuntimeError("oracle kv_append failed: %d" % st)

@@ -22,14 +22,14 @@ GLM_ERR_NULL, GLM_ERR_GEOM, GLM_ERR_ALIGN, GLM_ERR_WORKSPACE = -1, -2, -3, -4
 GLM_ERR_PLAN_MISMATCH, GLM_ERR_RANGE, GLM_ERR_HIP, GLM_ERR_ALLOC = -5, -6, -7, -8
 
 EXPORTS = (
-    "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather",
+    "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather", "glm_kv_append",
     "glm_plan_create", "glm_plan_create_host", "glm_plan_destroy", "glm_plan_workspace_bytes",
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
     "glm_profile_enable", "glm_profile_reset", "glm_profile_read", "glm_bench_mfma", "glm_bench_copy",
 )
-KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4}
+KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5}
 
 
 class glm_geom(ctypes.Structure):
@@ -66,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.glm_kv_fork_copy.restype = ctypes.c_int
     lib.glm_kv_gather.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
     lib.glm_kv_gather.restype = ctypes.c_int
+    lib.glm_kv_append.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
+    lib.glm_kv_append.restype = ctypes.c_int
     lib.glm_plan_create.argtypes = [glm_geom, vp, i32, vp, vp, i32, vp, ctypes.POINTER(ctypes.c_int)]
     lib.glm_plan_create.restype = vp
     lib.glm_plan_create_host.argtypes = [glm_geom, vp, i32, vp, vp, i32, ctypes.POINTER(ctypes.c_int)]
@@ -280,3 +282,12 @@ def glm_bench_mfma(sink_dev, workgroups: int, iters: int, hip_stream=None) -> No
 
 def glm_bench_copy(src_dev, dst_dev, nbytes: int, hip_stream=None) -> None:
     _check(_lib.glm_bench_copy(_dev(src_dev), _dev(dst_dev), nbytes, _stream(hip_stream)), "glm_bench_copy")
+
+
+def glm_kv_append(g, kv_pool_dev, k_new_dev, v_new_dev, slot_mapping_dev, n_tokens: int, hip_stream=None,
+                  check: bool = True) -> int:
+    st = _lib.glm_kv_append(geom(g), _dev(kv_pool_dev), _dev(k_new_dev), _dev(v_new_dev), _dev(slot_mapping_dev),
+                            n_tokens, _stream(hip_stream))
+    if check:
+        _check(st, "glm_kv_append")
+    return st

@@ -41,6 +41,7 @@ struct AttnArgs {
     int32_t mode;
     int32_t n_split, chunk_blocks, row_tiles;   // implicit modes
     int32_t items_per_xcd;      // planned prefill: work items per XCD (list length / 8)
+    int32_t q_rows;             // rows of Q / out (bounds the row index derived from cu_q_lens)
     float scale_log2;           // scale * log2(e)
 };
 
@@ -156,7 +157,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     if (valid) {
         if (a.cu_q_lens) {
             const int ctx = a.seq_lens[c.rep] - c.n_mem;
-            q_row = (int64_t)a.cu_q_lens[c.rep] + mi;
+            q_row = min(max(a.cu_q_lens[c.rep] + mi, 0), a.q_rows - 1);   // stays inside Q / out whatever cu_q_lens holds
             limit = ctx + mi + 1;
         } else {
             const int r = c.mem_off < 0 ? c.rep : a.members[c.mem_off + mi];
@@ -990,6 +991,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
     a.tables = block_tables_dev;
     a.seq_lens = seq_lens_dev;
     a.cu_q_lens = cu_q_lens_dev;
+    a.q_rows = sum_q;
     a.max_blocks = max_blocks; a.B = B; a.Hkv = Hkv; a.Hq = Hq; a.G = G; a.num_blocks = g.num_blocks;
     a.scale_log2 = scale * 1.44269504088896340736f;
 

@@ -54,6 +54,26 @@ __global__ void __launch_bounds__(kCopyThreads) fork_copy_kernel(u32x4 *__restri
     for (int p = threadIdx.x; p < total; p += kCopyThreads) dp[p] = sp[p];
 }
 
+// grid = n_tokens: one workgroup scatters one token's K and V rows (2 * Hkv * row_pieces 16-byte pieces)
+// to its slot; piece p = (plane, head, c) goes to block + (plane*Hkv + head) * slab + offset * row + c.
+__global__ void __launch_bounds__(kCopyThreads) append_kernel(u32x4 *__restrict__ pool, const u32x4 *__restrict__ k_new,
+                                                              const u32x4 *__restrict__ v_new,
+                                                              const int64_t *__restrict__ slots, int hkv, int row_pieces,
+                                                              int64_t pieces_per_block, int64_t num_slots) {
+    const int64_t tok = blockIdx.x;
+    const int64_t slot = slots[tok];
+    if (slot < 0 || slot >= num_slots) return;                    // padding, or out of range: never write outside the pool
+    const int64_t blk = slot / kBlockSize;
+    const int off = (int)(slot % kBlockSize);
+    const int per_plane = hkv * row_pieces;
+    for (int p = threadIdx.x; p < 2 * per_plane; p += kCopyThreads) {
+        const int plane = p / per_plane, q = p % per_plane;
+        const int head = q / row_pieces, c = q % row_pieces;
+        const u32x4 v = (plane ? v_new : k_new)[tok * per_plane + q];
+        pool[blk * pieces_per_block + ((int64_t)(plane * hkv + head) * kBlockSize + off) * row_pieces + c] = v;
+    }
+}
+
 namespace {
 
 int validate_ids(const int32_t *ids_dev, int32_t n, int64_t upper, bool distinct, std::vector<int32_t> *keep,
@@ -144,3 +164,41 @@ int glm_kv_fork_copy(glm_geom g, void *kv_pool_dev, const int32_t *src_ids_dev, 
 }
 
 }  // extern "C"
+
+extern "C" int glm_kv_append(glm_geom g, void *kv_pool_dev, const void *k_new_dev, const void *v_new_dev,
+                             const int64_t *slot_mapping_dev, int32_t n_tokens, void *hip_stream) {
+    if (int st = check_geom(g)) return st;
+    if (n_tokens < 0) return GLM_ERR_GEOM;
+    if (n_tokens == 0) return GLM_OK;
+    if (!kv_pool_dev || !k_new_dev || !v_new_dev || !slot_mapping_dev) return GLM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(kv_pool_dev) | reinterpret_cast<uintptr_t>(k_new_dev) |
+         reinterpret_cast<uintptr_t>(v_new_dev)) & 15u)
+        return GLM_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t num_slots = (int64_t)g.num_blocks * g.block_size;
+    if (validate_enabled()) {
+        try {
+            std::vector<int64_t> h(n_tokens);
+            hipError_t e = hipStreamSynchronize(st);
+            if (e == hipSuccess) e = hipMemcpy(h.data(), slot_mapping_dev, (size_t)n_tokens * 8, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return set_hip_error(e);
+            std::vector<int64_t> used;
+            for (int64_t v : h) {
+                if (v >= num_slots) return GLM_ERR_RANGE;
+                if (v >= 0) used.push_back(v);
+            }
+            std::sort(used.begin(), used.end());
+            if (std::adjacent_find(used.begin(), used.end()) != used.end()) return GLM_ERR_RANGE;
+        } catch (...) {
+            return GLM_ERR_ALLOC;
+        }
+    }
+    const int row_pieces = g.head_dim * 2 / 16;
+    const int64_t pieces = 2LL * g.num_kv_heads * g.block_size * row_pieces;
+    ProfileScope prof(kKernelAppend, st);
+    hipLaunchKernelGGL(append_kernel, dim3(n_tokens), dim3(kCopyThreads), 0, st, (u32x4 *)kv_pool_dev,
+                       (const u32x4 *)k_new_dev, (const u32x4 *)v_new_dev, slot_mapping_dev, g.num_kv_heads, row_pieces,
+                       pieces, num_slots);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}

@@ -190,3 +190,29 @@ def test_blocks_beyond_4_gib_of_pool():
     exp[6, :, :, :5] = before[2, :, :, :5]
     np.testing.assert_array_equal(gu.host_u16(pool[off:off + 8]), exp)
     np.testing.assert_array_equal(gu.host_u16(staged), exp[5:7])
+
+
+@pytest.mark.parametrize("hkv,d", [(8, 128), (2, 64)])
+def test_kv_append_bit_exact_then_attention(hkv, d):
+    """The new tokens' K/V are appended by the library, then prefill attends them: same result as the oracle
+    on a pool filled by the oracle's append."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_prefill(5400 + d, prefix_groups=[[0, 1, 2]], prefix_tokens=[64], q_lens=[37, 1, 20, 9], num_q_heads=4 * hkv,
+                         num_kv_heads=hkv, head_dim=d)
+    slots = W.new_token_slots(w)
+    rng = np.random.default_rng(1)
+    k_new = W.f32_to_bf16_bits(rng.standard_normal((w.sum_q, hkv, d), dtype=np.float32))
+    v_new = W.f32_to_bf16_bits(rng.standard_normal((w.sum_q, hkv, d), dtype=np.float32))
+    slots_pad = np.concatenate([slots[:5], [-1], slots[5:]]).astype(np.int64)       # one padding token in the batch
+    k_pad = np.concatenate([k_new[:5], k_new[:1], k_new[5:]]); v_pad = np.concatenate([v_new[:5], v_new[:1], v_new[5:]])
+    ref_pool = w.pool.copy()
+    oracle.kv_append(w.geom, ref_pool, k_pad, v_pad, slots_pad)
+    dw = gu.DeviceWorkload(w)
+    glm.glm_kv_append(w.geom, dw.pool, gu.dev(k_pad), gu.dev(v_pad), torch.from_numpy(slots_pad).cuda(), slots_pad.size)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(dw.pool), ref_pool)
+    got = dw.prefill(plan=None)
+    ref = oracle.attention(w.geom, ref_pool, w.q, w.block_tables, w.seq_lens, w.scale, cu_q_lens=w.cu_q_lens)
+    assert np.abs(got - ref).max() <= gu.TOL
+    assert glm.glm_kv_append(w.geom, dw.pool, gu.dev(k_pad), gu.dev(v_pad), torch.from_numpy(slots_pad).cuda(), 0) == 0

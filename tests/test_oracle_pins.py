@@ -250,3 +250,37 @@ def test_gather_matches_indexing_and_inverts():
     both = np.zeros_like(src)
     oracle.gather(geom, src, np.array([1, 3], np.int32), both, np.array([8, 4], np.int32))
     np.testing.assert_array_equal(both[[8, 4]], src[[1, 3]])
+
+
+def test_kv_append_matches_indexing_and_leaves_the_rest():
+    rng = np.random.default_rng(8)
+    geom = W.Geometry(6, 4, 3, 3, 8)
+    pool = rng.integers(0, 65536, size=(6, 2, 3, 4, 8), dtype=np.uint16)
+    k_new = rng.integers(0, 65536, size=(5, 3, 8), dtype=np.uint16)
+    v_new = rng.integers(0, 65536, size=(5, 3, 8), dtype=np.uint16)
+    slots = np.array([9, 2, -1, 23, 0], np.int64)
+    ref = pool.copy()
+    for i, s in enumerate(slots):
+        if s >= 0:
+            ref[s // 4, 0, :, s % 4, :] = k_new[i]
+            ref[s // 4, 1, :, s % 4, :] = v_new[i]
+    got = pool.copy()
+    oracle.kv_append(geom, got, k_new, v_new, slots)
+    np.testing.assert_array_equal(got, ref)
+    assert (got != pool).sum() <= 4 * 2 * 3 * 8
+
+
+def test_new_token_slots_point_at_the_rows_attention_reads_last():
+    w = W.custom_prefill(12, prefix_groups=[[0, 1]], prefix_tokens=[8], q_lens=[3, 5], num_q_heads=2, num_kv_heads=1,
+                         head_dim=8, block_size=4)
+    slots = W.new_token_slots(w)
+    assert slots.shape == (8,)
+    # rewriting the new tokens' rows with what is already there changes nothing
+    k_new = np.stack([w.pool[s // 4, 0, :, s % 4, :] for s in slots]); v_new = np.stack([w.pool[s // 4, 1, :, s % 4, :] for s in slots])
+    pool = w.pool.copy()
+    oracle.kv_append(w.geom, pool, k_new, v_new, slots)
+    np.testing.assert_array_equal(pool, w.pool)
+    wd = _small_decode(13, [2, 6], prefix=8)
+    sd = W.new_token_slots(wd)
+    for r in range(2):
+        L = int(wd.seq_lens[r]); assert sd[r] == wd.block_tables[r, (L - 1) // 4] * 4 + (L - 1) % 4

@@ -436,5 +436,18 @@ def churn_step(w: Workload, step: int, *, n_fork: int = 32, readmit_frac: float 
                      evict, readmit, tables)
 
 
+def new_token_slots(w: Workload) -> np.ndarray:
+    """Token slots (block_id * block_size + offset, int64) of every request's new tokens, in Q row order:
+    decode: the one token at position seq_len-1; prefill: positions seq_len-q_len .. seq_len-1."""
+    bs = w.geom.block_size
+    out = []
+    for r in range(w.B):
+        L = int(w.seq_lens[r])
+        ql = 1 if w.q_lens is None else int(w.q_lens[r])
+        for pos in range(L - ql, L):
+            out.append(-1 if pos < 0 else int(w.block_tables[r, pos // bs]) * bs + pos % bs)
+    return np.asarray(out, np.int64)
+
+
 def make_config(index: int, seed: Optional[int] = None) -> Workload:
     return (tiny_decode, llama8b_decode, prefill_on_prefix, tree_decode_70b, eviction_churn)[index](seed)
