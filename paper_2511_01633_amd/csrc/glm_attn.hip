@@ -79,6 +79,7 @@ __device__ __forceinline__ int wave_max(int v) {
 // keys): with thousands of keys the rounding of single weights averages out far below the
 // error bound, and this kernel is MFMA bound there.
 constexpr int kSplitLimit = 1024;
+constexpr float kLazyLog2 = 8.0f;          // slack of the softmax reference, in units of log2
 constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format, no swizzle
 
 template <int D>
@@ -205,10 +206,20 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
     const int64_t slab = (int64_t)kBlockSize * D;
     const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
-    auto phys = [&](int b) -> int64_t {
-        const int bi = min(b, end_blk - 1);
-        const int id = __builtin_amdgcn_readfirstlane(table[bi]);
-        return (int64_t)min(max(id, 0), a.num_blocks - 1);
+    // Physical ids of the run, 64 blocks per vector register (lane i holds block c.b0 + 64 j + i), the next
+    // 64 requested when the current ones come into use: the tile loop then takes its ids with v_readlane
+    // and never waits for a table fetch.  Positions past the last block repeat it (prefetches run off the end).
+    auto load_ids = [&](int first) -> int { return table[max(min(first + lane, end_blk - 1), 0)]; };
+    auto clamp_id = [&](int id) -> int64_t { return (int64_t)min(max(id, 0), a.num_blocks - 1); };   // applied at use
+    int ids_cur = load_ids(c.b0), ids_nxt = load_ids(c.b0 + 64);
+    int id_pos = 0;                                        // blocks handed out so far
+    int64_t idA_next = 0, idB_next = 0;
+    auto next_pair = [&]() __attribute__((always_inline)) {
+        const int i = id_pos & 63;
+        if (i == 0 && id_pos > 0) { ids_cur = ids_nxt; ids_nxt = load_ids(c.b0 + id_pos + 64); }
+        idA_next = clamp_id(__builtin_amdgcn_readlane(ids_cur, i));
+        idB_next = clamp_id(__builtin_amdgcn_readlane(ids_cur, i + 1));
+        id_pos += 2;
     };
 
     // Global loads go through buffer descriptors: one descriptor per block (base = the block, range =
@@ -291,7 +302,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // FAST steps have no masking and no conditional prefetch, so that the MFMAs of QK^T(t+1) and the
     // exponentials of tile t share one basic block and get interleaved by the scheduler.
     f32x16 sT;
-    int64_t idA_next = 0, idB_next = 0;
     auto step = [&](auto fast_tag, auto split_tag, int t, int buf_t, int buf_t1, int buf_t2) {
         constexpr bool FAST = decltype(fast_tag)::value;
         constexpr bool SPLIT = decltype(split_tag)::value;
@@ -306,26 +316,29 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         float m_tile = sT[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
-        const float m_other = __shfl_xor(m_tile, 32);      // in flight while the next tile is staged below
+        m_tile *= a.scale_log2;                            // this lane's half of the row
         if (FAST || t + 2 < ntiles) {
             write_stage(buf_t2, t + 2, !FAST);
             if (FAST || t + 3 < ntiles) {
                 issue_loads(idA_next, idB_next);
-                if (FAST || t + 4 < ntiles) { idA_next = phys(c.b0 + 2 * t + 8); idB_next = phys(c.b0 + 2 * t + 9); }
+                if (FAST || t + 4 < ntiles) next_pair();
             }
         }
-        m_tile = fmaxf(m_tile, m_other) * a.scale_log2;
-        const float m_new = fmaxf(m_run, m_tile);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        if (__any(m_new > m_run)) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        // m_run is the reference the exponentials are taken against, not necessarily the running maximum:
+        // it moves (and the accumulator is rescaled) only when some score exceeds it by more than
+        // kLazyLog2, so weights stay <= 2^kLazyLog2 and the quotient acc / l is unchanged.  The common
+        // path needs no exchange between the two lanes of a row.
+        if (__any(m_tile > m_run + kLazyLog2)) {
+            const float m_new = fmaxf(m_run, fmaxf(m_tile, __shfl_xor(m_tile, 32)));
+            const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
             l_run *= alpha;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+            m_run = m_new;
         }
-        m_run = m_new;
+        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
 
         f32x16 s_next = sT;
         if (FAST || t + 1 < ntiles) s_next = qk(buf_t1);
@@ -369,12 +382,13 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
 
     auto run = [&](auto split_tag) {
         // prologue: stage tiles 0 and 1, compute the scores of tile 0, have tile 2 in flight
-        issue_loads(phys(c.b0), phys(c.b0 + 1));
-        if (ntiles > 1) { idA_next = phys(c.b0 + 2); idB_next = phys(c.b0 + 3); }
+        next_pair();
+        issue_loads(idA_next, idB_next);
+        if (ntiles > 1) next_pair();
         write_stage(0, 0, true);
         if (ntiles > 1) {
             issue_loads(idA_next, idB_next);
-            if (ntiles > 2) { idA_next = phys(c.b0 + 4); idB_next = phys(c.b0 + 5); }
+            if (ntiles > 2) next_pair();
         }
         __syncthreads();
         sT = qk(0);
@@ -382,7 +396,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             write_stage(1, 1, true);
             if (ntiles > 2) {
                 issue_loads(idA_next, idB_next);
-                if (ntiles > 3) { idA_next = phys(c.b0 + 6); idB_next = phys(c.b0 + 7); }
+                if (ntiles > 3) next_pair();
             }
         }
         __syncthreads();

@@ -208,22 +208,42 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     // Cooperative workgroups are MFMA bound and each chunk costs every member a partial result, so they
     // are cut only as far as filling the chip's workgroup slots (2 per CU) one and a half times requires
     // (measured on the 70B-shaped tree: fewer, longer chunks leave a ragged last round).
-    int64_t units = 0, units_coop = 0;
+    int64_t units_coop = 0;
     for (auto &s : segs) {
         const int64_t rows = (int64_t)s.members.size() * G;
         if (is_coop(rows)) units_coop += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kCoopRows);
-        else units += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kRowsPerWave);
     }
-    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 256 * 7);
-    int32_t cb = (int32_t)std::max<int64_t>(1, units * p.g.num_kv_heads / std::max(1, target));
-    cb = std::min(std::max(cb, env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8)), env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64));
-    cb = (cb + 1) & ~1;   // whole 32-token tiles
-    if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb = std::max(1, forced);
+    // Wave-private items all start together when the launch fits the chip's wave slots, and the launch
+    // ends with its slowest wave.  Per-wave timelines on MI355X (64 branches on 4 prefixes, d = 128)
+    // give an item of n tiles a relative duration of n + 2.4 when it is one of the row tiles of a run
+    // shared by 17..127 rows (the tiles stream the same K/V, three of four find it in L2) and of
+    // 1.16 (n + 3) when it streams alone.  Both chunk lengths are derived from one duration: the
+    // shortest for which the launch still is one round.
+    const int min_cb = env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8), max_cb = env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64);
+    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 2040);
+    auto clamp_cb = [&](int tiles) { return std::min(std::max(2 * tiles, min_cb), max_cb); };
+    auto count_items = [&](int32_t cb_fam, int32_t cb_one) {
+        int64_t n = 0;
+        for (auto &s : segs) {
+            const int64_t rows = (int64_t)s.members.size() * G;
+            if (is_coop(rows)) continue;
+            n += (int64_t)ceil_div(s.b1 - s.b0, rows > kRowsPerWave ? cb_fam : cb_one) * ceil_div(rows, kRowsPerWave);
+        }
+        return n * p.g.num_kv_heads;
+    };
+    int32_t cb_family = max_cb, cb_single = max_cb;
+    for (int nf = 1; nf <= 64; ++nf) {
+        const int ns = std::max(1, (int)((nf + 2.4) / 1.16 - 3.0 + 0.5));
+        cb_family = clamp_cb(nf);
+        cb_single = clamp_cb(ns);
+        if (count_items(cb_family, cb_single) <= target) break;
+    }
+    if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb_family = cb_single = std::max(1, forced);
     const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 3);
     int32_t cb_coop = (int32_t)std::max<int64_t>(32, units_coop * p.g.num_kv_heads / std::max(1, target_coop));
     cb_coop = (cb_coop + 1) & ~1;
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
-    auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : cb; };
+    auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };
 
     std::vector<std::vector<int32_t>> per_req(B);
     std::vector<Work> coop;
