@@ -65,43 +65,56 @@ __device__ __forceinline__ int wave_max(int v) {
 // Cooperative kernel: prefill on a cached prefix, and decode runs shared by >= 128 rows.
 //
 // One workgroup = 4 waves x 32 query rows that all see the same run of blocks.  K/V tiles of
-// two blocks (32 tokens) are fetched once per workgroup with coalesced 16-byte loads, staged in
-// a double-buffered LDS tile (one barrier per tile) and consumed by all four waves with
-// v_mfma_f32_32x32x16_bf16:
+// two blocks (32 tokens) are fetched once per workgroup, straight from global memory into a
+// four-stage LDS ring (global_load_lds_dwordx4: lane l of a wave instruction deposits 16 bytes at
+// base + 16 l; no staging registers, no LDS write instructions), one barrier per tile, and are
+// consumed by all four waves with v_mfma_f32_32x32x16_bf16:
 //   S^T[32 tokens][32 rows] = K . Q^T    A = K rows from LDS (lane = token, 16 B = half a k-step),
 //                                         B = Q^T in registers for the whole item
-//   softmax per row                       a row is lane % 32; its two lanes exchange through one shuffle
+//   softmax per row                       a row is lane % 32 and lane % 32 + 32
 //   O^T[d][32 rows] += V^T . P^T          A = V^T through ds_read_b64_tr_b16, B = P^T = the registers
 //                                         S^T came out in (k-step s takes registers 8s..8s+7)
-// Two workgroups fit a CU (<= 256 VGPRs, 36 KiB LDS each), so one wave's softmax overlaps the
+// LDS rows are unpadded (2 D bytes); instead the 16-byte chunks of a row are permuted by XOR with a
+// function of the row, applied to the global address on the way in (free: every lane of a load
+// addresses memory on its own) and to the LDS address on the way out:
+//   K: chunk c of row r sits at c ^ (r & 15)            (D = 64: c ^ ((r >> 1) & 7))
+//   V: chunk c of row r sits at c ^ ((r & 3) << 1)      (D = 64: c ^ (((r >> 1) & 1) << 1))
+// which makes the 16 lanes of a K read and the 32 lanes of a transposed V read hit distinct banks.
+// Two workgroups fit a CU (<= 256 VGPRs, 64 KiB LDS each), so one wave's softmax overlaps the
 // other wave's MFMAs on every SIMD.
 // P is split into bf16 head + remainder only while the run is short (<= kSplitLimit visible
 // keys): with thousands of keys the rounding of single weights averages out far below the
 // error bound, and this kernel is MFMA bound there.
 constexpr int kSplitLimit = 1024;
 constexpr float kLazyLog2 = 8.0f;          // slack of the softmax reference, in units of log2
-constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format, no swizzle
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {       // s_waitcnt vmcnt(N) only (gfx9 encoding)
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
 
 template <int D>
 __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     constexpr int T = 32;                      // tokens per tile
-    constexpr int KSTR = D + 8;                // LDS row pitch of K in elements
-    constexpr int VSTR = D + 16;               // LDS row pitch of V
+    constexpr int ROWB = 2 * D;                // bytes of a K or V row
+    constexpr int CH = ROWB / 16;              // 16-byte chunks per row
+    constexpr int RPI = 1024 / ROWB;           // rows one wave instruction brings
+    constexpr int IPP = T / RPI;               // wave instructions per plane of a tile
+    constexpr int IPW = 2 * IPP / 4;           // wave instructions per wave per tile
+    constexpr int PLANE_B = T * ROWB;          // bytes of the K (or V) part of a stage
+    constexpr int STAGE_B = 2 * PLANE_B;
+    constexpr int NS = 4;                      // ring stages
     constexpr int KSTEPS = D / 16;             // k-steps of S^T = K.Q^T
     constexpr int DT = D / 32;                 // 32-wide d tiles of O^T
-    constexpr int PLANE_PIECES = T * D / 8;    // 16-byte pieces of one plane of a tile
-    constexpr int BLOCK_PIECES = 16 * D / 8;
-    constexpr int PPT = 2 * PLANE_PIECES / 256;
-    static_assert(2 * PLANE_PIECES % 256 == 0, "tile must split evenly over the threads");
+    static_assert(IPW >= 1 && 16 % RPI == 0, "a wave instruction must stay inside one block");
 
-    __shared__ __attribute__((aligned(16))) __bf16 k_lds[3][T * KSTR];
-    __shared__ __attribute__((aligned(16))) __bf16 v_lds[3][T * VSTR];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE_B];
     __shared__ int wave_lim[4], wave_min[4];
 
     const int tid = threadIdx.x;
     __builtin_assume(tid >= 0 && tid < 256);
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n32 = lane & 31;                 // row within the wave's 32 rows / token within a tile
     const int h2 = lane >> 5;                  // which half of the k slots this lane holds
 
@@ -204,8 +217,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     float l_run = 0.f;      // this lane's share of the row sum (its 16 of every 32 tokens)
 
     const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
-    const int64_t slab = (int64_t)kBlockSize * D;
-    const int64_t blk_elems = 2 * (int64_t)a.Hkv * slab;
+    const int64_t blk_bytes = 2 * (int64_t)a.Hkv * kBlockSize * ROWB;
     // Physical ids of the run, 64 blocks per vector register (lane i holds block c.b0 + 64 j + i), the next
     // 64 requested when the current ones come into use: the tile loop then takes its ids with v_readlane
     // and never waits for a table fetch.  Positions past the last block repeat it (prefetches run off the end).
@@ -222,87 +234,83 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         id_pos += 2;
     };
 
-    // Global loads go through buffer descriptors: one descriptor per block (base = the block, range =
-    // its bytes, built with scalar instructions), and per thread a fixed 32-bit byte offset for each
-    // of its PPT 16-byte pieces of a tile - no per-load 64-bit vector address arithmetic.
-    u32x4 stage[PPT];
-    int piece_off[PPT];
-    bool piece_b[PPT];
+    // ---- loads: wave instruction q = wave * IPW + i of a tile brings rows g*RPI .. of plane q / IPP;
+    // lane l fills chunk position l % CH of tile row g*RPI + l / CH with the chunk the permutation puts there
+    auto kswz = [](int row) -> int { return (row >> (D == 64 ? 1 : 0)) & (CH - 1); };
+    auto vswz = [](int row) -> int { return D == 64 ? ((row >> 1) & 1) << 1 : (row & 3) << 1; };
+    int ld_off[IPW];        // byte offset inside a block of this lane's 16 bytes
+    int ld_rb[IPW];         // their row inside the block
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) {
-        const int gp = tid + 256 * i;
-        const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
-        piece_b[i] = (p / BLOCK_PIECES) != 0;
-        piece_off[i] = (((plane * a.Hkv + kvh) * (int)slab) + (p % BLOCK_PIECES) * 8) * 2;
+    for (int i = 0; i < IPW; ++i) {
+        const int q = wave * IPW + i;
+        const int plane = q / IPP, g = q % IPP;
+        const int r = g * RPI + lane / CH;
+        const int src = (lane % CH) ^ (plane ? vswz(r) : kswz(r));
+        ld_rb[i] = r % kBlockSize;
+        ld_off[i] = ((plane * a.Hkv + kvh) * kBlockSize + ld_rb[i]) * ROWB + src * 16;
     }
-    const int blk_bytes = (int)(blk_elems * 2);
-    auto issue_loads = [&](int64_t idA, int64_t idB) {
-        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.pool + idA * blk_elems), 0, blk_bytes, kBufferFlags);
-        const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.pool + idB * blk_elems), 0, blk_bytes, kBufferFlags);
-#pragma unroll
-        for (int i = 0; i < PPT; ++i)
-            stage[i] = __builtin_amdgcn_raw_buffer_load_b128(piece_b[i] ? rb : ra, piece_off[i], 0, 0);
-    };
-    auto write_stage = [&](int buf, int t, bool maybe_tail) {
+    const unsigned char *pool_b = reinterpret_cast<const unsigned char *>(a.pool);
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)ring;
+    // requests tile t (blocks idA, idB) into ring stage t % NS.  On the last tile, rows that no query row
+    // can see are fetched from the block's last visible row instead: their weights are 0, and 0 times
+    // whatever an unwritten row holds must not become NaN.
+    auto issue_loads = [&](int t, int64_t idA, int64_t idB, bool maybe_tail) __attribute__((always_inline)) {
+        const int stage_off = (t & (NS - 1)) * STAGE_B;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
-        if (maybe_tail && pos0 + T > wg_lim) {
-            // last tile: V rows no query row can see must be finite (their weight is 0 and 0 * NaN is NaN)
+        const bool tail = maybe_tail && pos0 + T > wg_lim;
 #pragma unroll
-            for (int i = 0; i < PPT; ++i) {
-                const int gp = tid + 256 * i;
-                const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
-                const int row = p / (D / 8), ch = p % (D / 8);
-                u32x4 v = stage[i];
-                if (plane) {
-                    if (pos0 + row >= wg_lim) v = u32x4{0u, 0u, 0u, 0u};
-                    *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = v;
-                } else {
-                    *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = v;
-                }
+        for (int i = 0; i < IPW; ++i) {
+            const int q = wave * IPW + i;
+            const int plane = q / IPP, g = q % IPP;
+            const int bb = (g * RPI) / kBlockSize;                                    // uniform
+            int off = ld_off[i];
+            if (tail) {
+                const int blk = min(c.b0 + 2 * t + bb, end_blk - 1);
+                const int vis = min(kBlockSize, wg_lim - blk * kBlockSize);          // >= 1
+                off -= max(ld_rb[i] - (vis - 1), 0) * ROWB;
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < PPT; ++i) {
-                const int gp = tid + 256 * i;
-                const int plane = gp / PLANE_PIECES, p = gp % PLANE_PIECES;
-                const int row = p / (D / 8), ch = p % (D / 8);
-                if (plane) *reinterpret_cast<u32x4 *>(&v_lds[buf][row * VSTR + ch * 8]) = stage[i];
-                else *reinterpret_cast<u32x4 *>(&k_lds[buf][row * KSTR + ch * 8]) = stage[i];
-            }
+            const unsigned char *blk = pool_b + (bb ? idB : idA) * blk_bytes;         // uniform
+            const uint32_t dst = ring_lds + stage_off + plane * PLANE_B + g * 1024;    // uniform
+            // Issued as assembly on purpose: the compiler would make every later LDS read wait for all
+            // outstanding loads of this kind; the waits are placed by hand (wait_vmcnt) before the barrier
+            // that publishes a tile.
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(off), "s"(blk)
+                         : "memory");      // m0: nothing else in this kernel reads it
         }
     };
 
-    // LDS offsets of this lane's transposed V reads.  The d columns of an O^T tile are split: lanes
-    // 0-15 of a half take columns 16*dt .. +15, lanes 16-31 take D/2 + 16*dt .. +15, which puts the
-    // two 16-lane groups on disjoint LDS banks.  Lane i of a group supplies row i/4, columns 4*(i%4) ..
-    const int v_rd = (4 * h2 + ((lane & 15) >> 2)) * VSTR + (D / 2) * ((lane >> 4) & 1) + 4 * (lane & 3);
-    const int k_rd = n32 * KSTR + 8 * h2;
+    // ---- reads: LDS byte offsets inside a stage, before the k-step / d-tile bits are XORed in
+    const int k_rd = n32 * ROWB + (((kswz(n32) & ~1) | (h2 ^ (kswz(n32) & 1))) << 4);
+    const int v_row = 4 * h2 + ((lane & 15) >> 2);
+    const int v_rd = PLANE_B + v_row * ROWB + ((lane >> 4) & 1) * (ROWB / 2) + ((lane & 3) >> 1) * 16 + (lane & 1) * 8 +
+                     (vswz(v_row) << 4);
 
-    // S^T = K . Q^T of the tile staged in buffer `buf`: one accumulator, KSTEPS dependent MFMAs
-    auto qk = [&](int buf) -> f32x16 {
-        const __bf16 *kt = k_lds[buf] + k_rd;
+    // S^T = K . Q^T of the tile in ring stage `stage`: one accumulator, KSTEPS dependent MFMAs
+    auto qk = [&](int stage) -> f32x16 {
+        const int kb = k_rd + stage * STAGE_B;
         f32x16 sT;
 #pragma unroll
         for (int i = 0; i < 16; ++i) sT[i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + 16 * ks);
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ring + (kb ^ (ks << 5)));
             sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[ks], sT, 0, 0, 0);
         }
         return sT;
     };
 
-    // Software pipeline over tiles, three LDS stages, one barrier per tile.  At the top of step t:
+    // Software pipeline over tiles.  At the top of step t:
     //   sT holds the raw scores of tile t (its QK^T ran during step t-1),
-    //   tile t+1 is staged in LDS, tile t+2 sits in the staging registers (its loads flew during step t-1).
-    // Step t stages tile t+2, requests tile t+3, starts QK^T of tile t+1 and, while those MFMAs run,
-    // does the softmax of tile t on the VALU; then PV of tile t.
+    //   tiles t and t+1 are complete in their ring stages, tile t+2 is in flight.
+    // Step t requests tile t+3 (into the stage tile t-1 left), starts QK^T of tile t+1 and, while those
+    // MFMAs run, does the softmax of tile t on the VALU; then PV of tile t; then waits for its own loads
+    // of tile t+2 and meets the other waves at the barrier.
     // FAST steps have no masking and no conditional prefetch, so that the MFMAs of QK^T(t+1) and the
     // exponentials of tile t share one basic block and get interleaved by the scheduler.
     f32x16 sT;
-    auto step = [&](auto fast_tag, auto split_tag, int t, int buf_t, int buf_t1, int buf_t2) {
+    auto step = [&](auto fast_tag, auto split_tag, int t) {
         constexpr bool FAST = decltype(fast_tag)::value;
         constexpr bool SPLIT = decltype(split_tag)::value;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
@@ -313,17 +321,14 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             for (int i = 0; i < 16; ++i)
                 if (pos0 + 8 * (i >> 2) + 4 * h2 + (i & 3) >= lim_eff) sT[i] = -INFINITY;
         }
+        if (FAST || t + 3 < ntiles) {
+            issue_loads(t + 3, idA_next, idB_next, !FAST);
+            if (FAST || t + 4 < ntiles) next_pair();
+        }
         float m_tile = sT[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
         m_tile *= a.scale_log2;                            // this lane's half of the row
-        if (FAST || t + 2 < ntiles) {
-            write_stage(buf_t2, t + 2, !FAST);
-            if (FAST || t + 3 < ntiles) {
-                issue_loads(idA_next, idB_next);
-                if (FAST || t + 4 < ntiles) next_pair();
-            }
-        }
         // m_run is the reference the exponentials are taken against, not necessarily the running maximum:
         // it moves (and the accumulator is rescaled) only when some score exceeds it by more than
         // kLazyLog2, so weights stay <= 2^kLazyLog2 and the quotient acc / l is unchanged.  The common
@@ -341,7 +346,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
 
         f32x16 s_next = sT;
-        if (FAST || t + 1 < ntiles) s_next = qk(buf_t1);
+        if (FAST || t + 1 < ntiles) s_next = qk((t + 1) & (NS - 1));
 
         float p[16];
 #pragma unroll
@@ -364,55 +369,43 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
                 }
             }
         l_run += psum;
-        const __bf16 *vt = v_lds[buf_t] + v_rd;
+        const int vb = v_rd + (t & (NS - 1)) * STAGE_B;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const __bf16 *va = vt + (16 * s) * VSTR + 16 * dt;
+                const unsigned char *va = ring + (vb ^ (dt << 5)) + (16 * s) * ROWB;
                 const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * VSTR));
+                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * ROWB));
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
                 acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
                 if (SPLIT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[s], acc[dt], 0, 0, 0);
             }
         sT = s_next;
-        __syncthreads();    // tile t is consumed, tile t+2 is staged: the next step may read / overwrite
+        // own loads of tile t+2 have landed (those of tile t+3, if any, may still fly) ...
+        if (FAST) wait_vmcnt<IPW>();
+        else wait_vmcnt<0>();
+        __syncthreads();    // ... and everybody's: tile t is consumed, tile t+2 is complete
     };
 
     auto run = [&](auto split_tag) {
-        // prologue: stage tiles 0 and 1, compute the scores of tile 0, have tile 2 in flight
+        // prologue: tiles 0, 1 and 2 requested, 0 and 1 complete, scores of tile 0 computed
         next_pair();
-        issue_loads(idA_next, idB_next);
-        if (ntiles > 1) next_pair();
-        write_stage(0, 0, true);
-        if (ntiles > 1) {
-            issue_loads(idA_next, idB_next);
-            if (ntiles > 2) next_pair();
-        }
+        issue_loads(0, idA_next, idB_next, true);
+        if (ntiles > 1) { next_pair(); issue_loads(1, idA_next, idB_next, true); }
+        if (ntiles > 2) { next_pair(); issue_loads(2, idA_next, idB_next, true); }
+        if (ntiles > 3) next_pair();
+        if (ntiles > 2) wait_vmcnt<IPW>();
+        else wait_vmcnt<0>();
         __syncthreads();
         sT = qk(0);
-        if (ntiles > 1) {
-            write_stage(1, 1, true);
-            if (ntiles > 2) {
-                issue_loads(idA_next, idB_next);
-                if (ntiles > 3) next_pair();
-            }
-        }
-        __syncthreads();
         // tiles that end at or below every row's limit need no mask; the last four steps take the
         // general path because their prefetches run off the end
         const int t_nomask = max(0, (min(wg_min, end_blk * kBlockSize) - c.b0 * kBlockSize) / T);
         const int t_fast = min(ntiles - 4, t_nomask);
-        int t = 0, b0 = 0, b1 = 1, b2 = 2;
-        for (; t < t_fast; ++t) {
-            step(std::true_type{}, split_tag, t, b0, b1, b2);
-            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
-        }
-        for (; t < ntiles; ++t) {
-            step(std::false_type{}, split_tag, t, b0, b1, b2);
-            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
-        }
+        int t = 0;
+        for (; t < t_fast; ++t) step(std::true_type{}, split_tag, t);
+        for (; t < ntiles; ++t) step(std::false_type{}, split_tag, t);
     };
     if (ntiles > 0) {
         if (split) run(std::true_type{});
