@@ -202,6 +202,14 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     for (int s = 0; s < KSTEPS; ++s) {
         if (valid) {
             qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 16 * s + 8 * h2);
+            // Long runs: the factor scale*log2(e) goes into Q (rounded to bf16 again), and the softmax
+            // reference into the accumulator the QK^T chain starts from, so that the MFMAs deliver the
+            // exponent itself.  The extra rounding of Q moves a single weight by ~1e-3 relative, which
+            // averages out over > kSplitLimit keys; short runs keep the exact path.
+            if (!split) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)((float)qreg[s][j] * a.scale_log2);
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
@@ -215,6 +223,10 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
     float m_run = -INFINITY;
     float l_run = 0.f;      // this lane's share of the row sum (its 16 of every 32 tokens)
+    float lazy_thr = -INFINITY;   // long runs: a row without a reference yet takes its first finite score as one
+    f32x16 c_init;          // what a QK^T chain starts from: 0, or minus the reference on long runs
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c_init[i] = 0.f;
 
     const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
     const int64_t blk_bytes = 2 * (int64_t)a.Hkv * kBlockSize * ROWB;
@@ -226,13 +238,16 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     int ids_cur = load_ids(c.b0), ids_nxt = load_ids(c.b0 + 64);
     int id_pos = 0;                                        // blocks handed out so far
     int64_t idA_next = 0, idB_next = 0;
-    auto next_pair = [&]() __attribute__((always_inline)) {
+    auto rotate_ids = [&]() __attribute__((always_inline)) {
+        if ((id_pos & 63) == 0 && id_pos > 0) { ids_cur = ids_nxt; ids_nxt = load_ids(c.b0 + id_pos + 64); }
+    };
+    auto next_pair_cur = [&]() __attribute__((always_inline)) {     // the caller has rotated at 64-block boundaries
         const int i = id_pos & 63;
-        if (i == 0 && id_pos > 0) { ids_cur = ids_nxt; ids_nxt = load_ids(c.b0 + id_pos + 64); }
         idA_next = clamp_id(__builtin_amdgcn_readlane(ids_cur, i));
         idB_next = clamp_id(__builtin_amdgcn_readlane(ids_cur, i + 1));
         id_pos += 2;
     };
+    auto next_pair = [&]() __attribute__((always_inline)) { rotate_ids(); next_pair_cur(); };
 
     // ---- loads: wave instruction q = wave * IPW + i of a tile brings rows g*RPI .. of plane q / IPP;
     // lane l fills chunk position l % CH of tile row g*RPI + l / CH with the chunk the permutation puts there
@@ -290,9 +305,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // S^T = K . Q^T of the tile in ring stage `stage`: one accumulator, KSTEPS dependent MFMAs
     auto qk = [&](int stage) -> f32x16 {
         const int kb = k_rd + stage * STAGE_B;
-        f32x16 sT;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sT[i] = 0.f;
+        f32x16 sT = c_init;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ring + (kb ^ (ks << 5)));
@@ -314,8 +327,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         constexpr bool FAST = decltype(fast_tag)::value;
         constexpr bool SPLIT = decltype(split_tag)::value;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
-        // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]; raw scores,
-        // the factor scale*log2(e) (> 0) is folded into the exponent
+        // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]
         if (!FAST && pos0 + T > lim_eff) {
 #pragma unroll
             for (int i = 0; i < 16; ++i)
@@ -323,34 +335,70 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         }
         if (FAST || t + 3 < ntiles) {
             issue_loads(t + 3, idA_next, idB_next, !FAST);
-            if (FAST || t + 4 < ntiles) next_pair();
+            if (FAST) next_pair_cur();
+            else if (t + 4 < ntiles) next_pair();
         }
         float m_tile = sT[0];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
-        m_tile *= a.scale_log2;                            // this lane's half of the row
+        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);       // this lane's half of the row
         // m_run is the reference the exponentials are taken against, not necessarily the running maximum:
         // it moves (and the accumulator is rescaled) only when some score exceeds it by more than
         // kLazyLog2, so weights stay <= 2^kLazyLog2 and the quotient acc / l is unchanged.  The common
         // path needs no exchange between the two lanes of a row.
-        if (__any(m_tile > m_run + kLazyLog2)) {
-            const float m_new = fmaxf(m_run, fmaxf(m_tile, __shfl_xor(m_tile, 32)));
-            const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
-            l_run *= alpha;
+        float m_use;
+        if (SPLIT) {
+            // sT holds raw scores; scale*log2(e) (> 0) is folded into the exponent below
+            m_tile *= a.scale_log2;
+            if (__any(m_tile > m_run + kLazyLog2)) {
+                const float m_new = fmaxf(m_run, fmaxf(m_tile, __shfl_xor(m_tile, 32)));
+                const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+                l_run *= alpha;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
-            m_run = m_new;
+                    for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+                m_run = m_new;
+            }
+            m_use = (m_run == -INFINITY) ? 0.f : m_run;
+        } else {
+            // sT holds exponents relative to the reference (c_init = -reference went into the MFMA chain)
+            if (__any(m_tile > lazy_thr)) {
+                const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
+                const float m_new = fmaxf(m_run, m_old + fmaxf(m_tile, __shfl_xor(m_tile, 32)));
+                const float m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
+                const float delta = m_new_use - m_old;
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { sT[i] -= delta; c_init[i] = -m_new_use; }
+                m_run = m_new;
+                lazy_thr = (m_new == -INFINITY) ? -INFINITY : kLazyLog2;
+            }
+            m_use = 0.f;
         }
-        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
 
+        // K fragments of tile t+1, requested before the exponentials so that they have landed when QK^T starts
+        bf16x8 kf[KSTEPS];
+        if (FAST || t + 1 < ntiles) {
+            const int kb = k_rd + ((t + 1) & (NS - 1)) * STAGE_B;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ring + (kb ^ (ks << 5)));
+        }
         f32x16 s_next = sT;
-        if (FAST || t + 1 < ntiles) s_next = qk((t + 1) & (NS - 1));
+        if (FAST || t + 1 < ntiles) {
+            s_next = c_init;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qreg[ks], s_next, 0, 0, 0);
+        }
 
         float p[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use));
+        for (int i = 0; i < 16; ++i)
+            p[i] = SPLIT ? __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use)) : __builtin_amdgcn_exp2f(sT[i]);
         bf16x8 p_hi[2], p_lo[2];
         float psum = 0.f;
 #pragma unroll
@@ -403,8 +451,15 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         // general path because their prefetches run off the end
         const int t_nomask = max(0, (min(wg_min, end_blk * kBlockSize) - c.b0 * kBlockSize) / T);
         const int t_fast = min(ntiles - 4, t_nomask);
+        // The fast steps run in stretches that end where the next 64 block ids come into use, so that the
+        // loop itself holds no vector memory load the compiler knows of (it would wait for it, and with
+        // it for every tile load in flight, at the end of each step).
         int t = 0;
-        for (; t < t_fast; ++t) step(std::true_type{}, split_tag, t);
+        while (t < t_fast) {
+            rotate_ids();
+            const int t_stop = min(t_fast, t + ((64 - (id_pos & 63)) >> 1));
+            for (; t < t_stop; ++t) step(std::true_type{}, split_tag, t);
+        }
         for (; t < ntiles; ++t) step(std::false_type{}, split_tag, t);
     };
     if (ntiles > 0) {
