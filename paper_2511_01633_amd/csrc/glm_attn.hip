@@ -17,6 +17,7 @@
 namespace glm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -269,8 +270,8 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // requests tile t (blocks idA, idB) into ring stage t % NS.  On the last tile, rows that no query row
     // can see are fetched from the block's last visible row instead: their weights are 0, and 0 times
     // whatever an unwritten row holds must not become NaN.
-    auto issue_loads = [&](int t, int64_t idA, int64_t idB, bool maybe_tail) __attribute__((always_inline)) {
-        const int stage_off = (t & (NS - 1)) * STAGE_B;
+    auto issue_loads = [&](int stage, int t, int64_t idA, int64_t idB, bool maybe_tail) __attribute__((always_inline)) {
+        const int stage_off = stage * STAGE_B;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
         const bool tail = maybe_tail && pos0 + T > wg_lim;
 #pragma unroll
@@ -302,6 +303,14 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     const int v_rd = PLANE_B + v_row * ROWB + ((lane >> 4) & 1) * (ROWB / 2) + ((lane & 3) >> 1) * 16 + (lane & 1) * 8 +
                      (vswz(v_row) << 4);
 
+    // the same with the k-step / d-tile bits in: the fast steps know their ring stage at compile time, so
+    // all that is left per read is an immediate offset
+    int k_addr[KSTEPS], v_addr[DT];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) k_addr[ks] = k_rd ^ (ks << 5);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) v_addr[dt] = v_rd ^ (dt << 5);
+
     // S^T = K . Q^T of the tile in ring stage `stage`: one accumulator, KSTEPS dependent MFMAs
     auto qk = [&](int stage) -> f32x16 {
         const int kb = k_rd + stage * STAGE_B;
@@ -323,8 +332,9 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // FAST steps have no masking and no conditional prefetch, so that the MFMAs of QK^T(t+1) and the
     // exponentials of tile t share one basic block and get interleaved by the scheduler.
     f32x16 sT;
-    auto step = [&](auto fast_tag, auto split_tag, int t) {
-        constexpr bool FAST = decltype(fast_tag)::value;
+    auto step = [&](auto stage_tag, auto split_tag, int t) {
+        constexpr int STAGE = decltype(stage_tag)::value;       // t % NS if the step is a fast one, else -1
+        constexpr bool FAST = STAGE >= 0;
         constexpr bool SPLIT = decltype(split_tag)::value;
         const int pos0 = (c.b0 + 2 * t) * kBlockSize;
         // lane (row n32, half h2) holds token 8*(i/4) + 4*h2 + i%4 of the tile in sT[i]
@@ -334,7 +344,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
                 if (pos0 + 8 * (i >> 2) + 4 * h2 + (i & 3) >= lim_eff) sT[i] = -INFINITY;
         }
         if (FAST || t + 3 < ntiles) {
-            issue_loads(t + 3, idA_next, idB_next, !FAST);
+            issue_loads(FAST ? ((STAGE + 3) & (NS - 1)) : ((t + 3) & (NS - 1)), t + 3, idA_next, idB_next, !FAST);
             if (FAST) next_pair_cur();
             else if (t + 4 < ntiles) next_pair();
         }
@@ -383,7 +393,11 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
 
         // K fragments of tile t+1, requested before the exponentials so that they have landed when QK^T starts
         bf16x8 kf[KSTEPS];
-        if (FAST || t + 1 < ntiles) {
+        if (FAST) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks)
+                kf[ks] = *reinterpret_cast<const bf16x8 *>(ring + k_addr[ks] + ((STAGE + 1) & (NS - 1)) * STAGE_B);
+        } else if (t + 1 < ntiles) {
             const int kb = k_rd + ((t + 1) & (NS - 1)) * STAGE_B;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ring + (kb ^ (ks << 5)));
@@ -412,17 +426,33 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
                     const __bf16 l = (__bf16)(p[8 * s + j] - hf);
                     p_lo[s][j] = l;
                     psum += hf + (float)l;
-                } else {
-                    psum += p[8 * s + j];   // > kSplitLimit keys: the rounding of single weights averages out
                 }
             }
+        if (!SPLIT) {
+            // > kSplitLimit keys: the rounding of single weights averages out; the row sum is taken from
+            // the rounded weights, two per v_dot2c_f32_bf16
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f;
+            ones[1] = (__bf16)1.0f;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                {
+                    bf16x2 pr;
+                    pr[0] = p_hi[s][2 * j];
+                    pr[1] = p_hi[s][2 * j + 1];
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                }
+        }
         l_run += psum;
         const int vb = v_rd + (t & (NS - 1)) * STAGE_B;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const unsigned char *va = ring + (vb ^ (dt << 5)) + (16 * s) * ROWB;
+                const unsigned char *va = FAST ? ring + v_addr[dt] + STAGE * STAGE_B + (16 * s) * ROWB
+                                               : ring + (vb ^ (dt << 5)) + (16 * s) * ROWB;
                 const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
                 const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * ROWB));
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -439,9 +469,9 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     auto run = [&](auto split_tag) {
         // prologue: tiles 0, 1 and 2 requested, 0 and 1 complete, scores of tile 0 computed
         next_pair();
-        issue_loads(0, idA_next, idB_next, true);
-        if (ntiles > 1) { next_pair(); issue_loads(1, idA_next, idB_next, true); }
-        if (ntiles > 2) { next_pair(); issue_loads(2, idA_next, idB_next, true); }
+        issue_loads(0, 0, idA_next, idB_next, true);
+        if (ntiles > 1) { next_pair(); issue_loads(1, 1, idA_next, idB_next, true); }
+        if (ntiles > 2) { next_pair(); issue_loads(2, 2, idA_next, idB_next, true); }
         if (ntiles > 3) next_pair();
         if (ntiles > 2) wait_vmcnt<IPW>();
         else wait_vmcnt<0>();
@@ -451,16 +481,25 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         // general path because their prefetches run off the end
         const int t_nomask = max(0, (min(wg_min, end_blk * kBlockSize) - c.b0 * kBlockSize) / T);
         const int t_fast = min(ntiles - 4, t_nomask);
+        static_assert(NS == 4, "the fast loop is unrolled over the ring stages");
         // The fast steps run in stretches that end where the next 64 block ids come into use, so that the
         // loop itself holds no vector memory load the compiler knows of (it would wait for it, and with
         // it for every tile load in flight, at the end of each step).
+        // They come four at a time, one per ring stage, so that every LDS address in them is a register plus
+        // an immediate; a stretch starts at a multiple of four (ids rotate when t + 4 is a multiple of 32).
         int t = 0;
-        while (t < t_fast) {
+        while (t + NS <= t_fast) {
             rotate_ids();
             const int t_stop = min(t_fast, t + ((64 - (id_pos & 63)) >> 1));
-            for (; t < t_stop; ++t) step(std::true_type{}, split_tag, t);
+            for (; t + NS <= t_stop; t += NS) {
+                step(std::integral_constant<int, 0>{}, split_tag, t);
+                step(std::integral_constant<int, 1>{}, split_tag, t + 1);
+                step(std::integral_constant<int, 2>{}, split_tag, t + 2);
+                step(std::integral_constant<int, 3>{}, split_tag, t + 3);
+            }
+            if (t < t_stop) break;      // fewer than four fast steps left: the general path takes them
         }
-        for (; t < ntiles; ++t) step(std::false_type{}, split_tag, t);
+        for (; t < ntiles; ++t) step(std::integral_constant<int, -1>{}, split_tag, t);
     };
     if (ntiles > 0) {
         if (split) run(std::true_type{});
