@@ -88,6 +88,7 @@ __device__ __forceinline__ int wave_max(int v) {
 // error bound, and this kernel is MFMA bound there.
 constexpr int kSplitLimit = 1024;
 constexpr float kLazyLog2 = 8.0f;          // slack of the softmax reference, in units of log2
+constexpr float kLazySum = 256.0f;         // 2^kLazyLog2: a lane's 16 weights sum to more only if a score is well above the reference
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {       // s_waitcnt vmcnt(N) only (gfx9 encoding)
@@ -224,7 +225,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
     float m_run = -INFINITY;
     float l_run = 0.f;      // this lane's share of the row sum (its 16 of every 32 tokens)
-    float lazy_thr = -INFINITY;   // long runs: a row without a reference yet takes its first finite score as one
     f32x16 c_init;          // what a QK^T chain starts from: 0, or minus the reference on long runs
 #pragma unroll
     for (int i = 0; i < 16; ++i) c_init[i] = 0.f;
@@ -332,6 +332,44 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // FAST steps have no masking and no conditional prefetch, so that the MFMAs of QK^T(t+1) and the
     // exponentials of tile t share one basic block and get interleaved by the scheduler.
     f32x16 sT;
+    float sum_thr = -1.0f;            // a row sum above this moves the reference; -1 until the row has one
+    auto weights = [&](auto split_tag, float m_use, bf16x8 (&hi)[2], bf16x8 (&lo)[2]) __attribute__((always_inline)) -> float {
+        constexpr bool SPLIT = decltype(split_tag)::value;
+        float psum = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = 8 * s2 + j;
+                const float pf = SPLIT ? __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use))
+                                       : __builtin_amdgcn_exp2f(sT[i]);
+                const __bf16 h = (__bf16)pf;
+                hi[s2][j] = h;
+                if (SPLIT) {
+                    const float hf = (float)h;
+                    const __bf16 l = (__bf16)(pf - hf);
+                    lo[s2][j] = l;
+                    psum += hf + (float)l;
+                }
+            }
+        if (!SPLIT) {
+            // > kSplitLimit keys: the rounding of single weights averages out; the row sum is taken from
+            // the rounded weights, two per v_dot2c_f32_bf16
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f;
+            ones[1] = (__bf16)1.0f;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bf16x2 pr;
+                    pr[0] = hi[s2][2 * j];
+                    pr[1] = hi[s2][2 * j + 1];
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                }
+        }
+        return psum;
+    };
     auto step = [&](auto stage_tag, auto split_tag, int t) {
         constexpr int STAGE = decltype(stage_tag)::value;       // t % NS if the step is a fast one, else -1
         constexpr bool FAST = STAGE >= 0;
@@ -348,49 +386,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             if (FAST) next_pair_cur();
             else if (t + 4 < ntiles) next_pair();
         }
-        float m_tile = sT[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);       // this lane's half of the row
-        // m_run is the reference the exponentials are taken against, not necessarily the running maximum:
-        // it moves (and the accumulator is rescaled) only when some score exceeds it by more than
-        // kLazyLog2, so weights stay <= 2^kLazyLog2 and the quotient acc / l is unchanged.  The common
-        // path needs no exchange between the two lanes of a row.
-        float m_use;
-        if (SPLIT) {
-            // sT holds raw scores; scale*log2(e) (> 0) is folded into the exponent below
-            m_tile *= a.scale_log2;
-            if (__any(m_tile > m_run + kLazyLog2)) {
-                const float m_new = fmaxf(m_run, fmaxf(m_tile, __shfl_xor(m_tile, 32)));
-                const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
-                l_run *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
-                m_run = m_new;
-            }
-            m_use = (m_run == -INFINITY) ? 0.f : m_run;
-        } else {
-            // sT holds exponents relative to the reference (c_init = -reference went into the MFMA chain)
-            if (__any(m_tile > lazy_thr)) {
-                const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
-                const float m_new = fmaxf(m_run, m_old + fmaxf(m_tile, __shfl_xor(m_tile, 32)));
-                const float m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
-                const float delta = m_new_use - m_old;
-                l_run *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { sT[i] -= delta; c_init[i] = -m_new_use; }
-                m_run = m_new;
-                lazy_thr = (m_new == -INFINITY) ? -INFINITY : kLazyLog2;
-            }
-            m_use = 0.f;
-        }
-
         // K fragments of tile t+1, requested before the exponentials so that they have landed when QK^T starts
         bf16x8 kf[KSTEPS];
         if (FAST) {
@@ -409,41 +404,48 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             for (int ks = 0; ks < KSTEPS; ++ks) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qreg[ks], s_next, 0, 0, 0);
         }
 
-        float p[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            p[i] = SPLIT ? __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use)) : __builtin_amdgcn_exp2f(sT[i]);
+        // The weights are taken against the reference m_run WITHOUT looking at the scores first (m_run is
+        // not necessarily the running maximum).  The row sums show afterwards whether some score was more
+        // than kLazyLog2 above the reference, and only then (rare) the reference moves: accumulator and sums
+        // are rescaled and this tile's weights taken again.  Weights thus stay <= 2^kLazyLog2 and the
+        // quotient acc / l is unchanged; the common path has no maximum, no exchange between the two lanes
+        // of a row and no branch between the QK^T MFMAs and the exponentials.
+        const float m_use = (SPLIT && m_run != -INFINITY) ? m_run : 0.f;
         bf16x8 p_hi[2], p_lo[2];
-        float psum = 0.f;
+        float psum = weights(split_tag, m_use, p_hi, p_lo);
+        if (__any(!(psum <= sum_thr))) {
+            float m_tile = sT[0];
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+            for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
+            float m_new, alpha, m_new_use;
+            if (SPLIT) {
+                // sT holds raw scores; scale*log2(e) (> 0) is folded into the exponent
+                m_new = fmaxf(m_run, m_tile * a.scale_log2);
+                m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
+                alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
+            } else {
+                // sT holds exponents relative to the reference (c_init = -reference went into the MFMA chain)
+                const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
+                m_new = fmaxf(m_run, m_old + m_tile);
+                m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
+                alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
+                const float delta = m_new_use - m_old;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const __bf16 h = (__bf16)p[8 * s + j];
-                p_hi[s][j] = h;
-                if (SPLIT) {
-                    const float hf = (float)h;
-                    const __bf16 l = (__bf16)(p[8 * s + j] - hf);
-                    p_lo[s][j] = l;
-                    psum += hf + (float)l;
+                for (int i = 0; i < 16; ++i) { sT[i] -= delta; c_init[i] = -m_new_use; }
+                if (FAST || t + 1 < ntiles) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s_next[i] -= delta;
                 }
             }
-        if (!SPLIT) {
-            // > kSplitLimit keys: the rounding of single weights averages out; the row sum is taken from
-            // the rounded weights, two per v_dot2c_f32_bf16
-            bf16x2 ones;
-            ones[0] = (__bf16)1.0f;
-            ones[1] = (__bf16)1.0f;
+            l_run *= alpha;
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                {
-                    bf16x2 pr;
-                    pr[0] = p_hi[s][2 * j];
-                    pr[1] = p_hi[s][2 * j + 1];
-                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-                }
+                for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+            m_run = m_new;
+            sum_thr = (m_new == -INFINITY) ? -1.0f : kLazySum;
+            psum = weights(split_tag, SPLIT ? m_new_use : 0.f, p_hi, p_lo);
         }
         l_run += psum;
         const int vb = v_rd + (t & (NS - 1)) * STAGE_B;
@@ -477,10 +479,10 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         else wait_vmcnt<0>();
         __syncthreads();
         sT = qk(0);
-        // tiles that end at or below every row's limit need no mask; the last four steps take the
-        // general path because their prefetches run off the end
+        // tiles that end at or below every row's limit need no mask and take the fast steps; their
+        // prefetches may run off the end of the run (the ids repeat the last block, the data is not used)
         const int t_nomask = max(0, (min(wg_min, end_blk * kBlockSize) - c.b0 * kBlockSize) / T);
-        const int t_fast = min(ntiles - 4, t_nomask);
+        const int t_fast = min(ntiles, t_nomask);
         static_assert(NS == 4, "the fast loop is unrolled over the ring stages");
         // The fast steps run in stretches that end where the next 64 block ids come into use, so that the
         // loop itself holds no vector memory load the compiler knows of (it would wait for it, and with
@@ -500,6 +502,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             if (t < t_stop) break;      // fewer than four fast steps left: the general path takes them
         }
         for (; t < ntiles; ++t) step(std::integral_constant<int, -1>{}, split_tag, t);
+        wait_vmcnt<0>();    // nothing may still be on its way into this workgroup's LDS when it ends
     };
     if (ntiles > 0) {
         if (split) run(std::true_type{});
