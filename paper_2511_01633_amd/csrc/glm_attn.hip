@@ -413,6 +413,18 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         const float m_use = (SPLIT && m_run != -INFINITY) ? m_run : 0.f;
         bf16x8 p_hi[2], p_lo[2];
         float psum = weights(split_tag, m_use, p_hi, p_lo);
+        // V^T fragments of tile t, requested before the check below so that they have landed when PV starts
+        const int vb = v_rd + (t & (NS - 1)) * STAGE_B;
+        bf16x8 vf[DT][2];
+        auto v_read = [&](int dt, int s) __attribute__((always_inline)) {
+            const unsigned char *va = FAST ? ring + v_addr[dt] + STAGE * STAGE_B + (16 * s) * ROWB
+                                           : ring + (vb ^ (dt << 5)) + (16 * s) * ROWB;
+            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * ROWB));
+            vf[dt][s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+#pragma unroll
+        for (int dt = 0; dt < DT / 2; ++dt) { v_read(dt, 0); v_read(dt, 1); }      // (the registers hold no more)
         if (__any(!(psum <= sum_thr))) {
             float m_tile = sT[0];
 #pragma unroll
@@ -448,18 +460,14 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
             psum = weights(split_tag, SPLIT ? m_new_use : 0.f, p_hi, p_lo);
         }
         l_run += psum;
-        const int vb = v_rd + (t & (NS - 1)) * STAGE_B;
+#pragma unroll
+        for (int dt = DT / 2; dt < DT; ++dt) { v_read(dt, 0); v_read(dt, 1); }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const unsigned char *va = FAST ? ring + v_addr[dt] + STAGE * STAGE_B + (16 * s) * ROWB
-                                               : ring + (vb ^ (dt << 5)) + (16 * s) * ROWB;
-                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 8 * ROWB));
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7));
-                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[s], acc[dt], 0, 0, 0);
-                if (SPLIT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[s], acc[dt], 0, 0, 0);
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], p_hi[s], acc[dt], 0, 0, 0);
+                if (SPLIT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], p_lo[s], acc[dt], 0, 0, 0);
             }
         sT = s_next;
         // own loads of tile t+2 have landed (those of tile t+3, if any, may still fly) ...
