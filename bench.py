@@ -227,6 +227,42 @@ def bench_churn(glm, W, w, steps, warmup, variants=4):
     return res
 
 
+def bench_cache_policy(glm, W):
+    """Host-side block manager on a synthetic three-agent call trace: block hit rate of the four-tier policy against
+    one LRU queue for everything (same manager, every block Priority IV), and calls per second."""
+    import zlib
+
+    def keys(names):
+        out, acc = [], b""
+        for n in names:
+            acc += b"/" + n.encode()
+            out.append((zlib.crc32(acc) | (zlib.adler32(acc) << 32)) or 1)
+        return out
+
+    trace = [(op[0], keys(op[1]), op[2], op[3]) if op[0] == "call" else op for op in W.agent_trace()]
+    res = {}
+    for name, flat in (("priority", False), ("single_lru", True)):
+        c = glm.Cache(96)
+        t0 = time.perf_counter()
+        calls = 0
+        for op in trace:
+            if op[0] == "end":
+                c.end_session(op[1])
+                continue
+            _, k, tiers, sess = op
+            r = c.acquire(k, [4] * len(k) if flat else tiers, sess, check=False)
+            if isinstance(r, int):
+                continue
+            c.release(r[0])
+            calls += 1
+        dt = time.perf_counter() - t0
+        st = c.stats()
+        res[name] = {"block_hit_rate": st["hits"] / max(1, st["hits"] + st["misses"]), "calls": calls,
+                     "calls_per_s": calls / dt, "evicted": [st["evicted_II"], st["evicted_III"], st["evicted_IV"]]}
+        c.close()
+    return res
+
+
 def reference_rates(glm):
     """MFMA-only rate and plain-copy bandwidth of this chip, measured with the library's reference kernels."""
     import torch
@@ -322,6 +358,7 @@ def main():
                                                 max(2, args.warmup // 4))
     if "churn" in only:
         extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+    extra["cache_policy"] = bench_cache_policy(glm, W)
     line["reference_rates"] = reference_rates(glm)
     line["extra"] = extra
     print(json.dumps(line))

@@ -1,0 +1,75 @@
+/*
+ * glm_cache.h - priority-tiered manager of the physical blocks of a paged KV pool (host code only).
+ *
+ * It decides WHICH physical block holds WHAT and what is dropped when the pool is full; the data itself
+ * is moved by the calls in glm.h (attention through the block tables it hands out, glm_kv_append for new
+ * tokens, glm_kv_fork_copy / glm_kv_gather for copies).  It implements the paper's four-tier
+ * priority-based eviction policy for prefix KV-cache blocks (Sec. 5.3) on top of prefix caching
+ * (Sec. 2.4: blocks of identical prefixes are reused):
+ *   Priority I    shared template prefixes of the agents: never evicted
+ *   Priority II   notebook content of a running query session: evicted last
+ *   Priority III  notebook content of finished sessions (Priority II is downgraded when the session ends)
+ *   Priority IV   cheap-to-regenerate parts (questions, missing-information requests): evicted first
+ * Eviction takes Priority IV, then III, then II, and the least recently used block inside a priority.
+ * What the section leaves open is settled as follows: a block that a running call references is not
+ * evictable; a block's time of use is the release of its last reference, the blocks of one call being
+ * stamped deepest first (a chain loses its tail before its head); a hit under a stronger priority keeps
+ * the stronger one.
+ *
+ * A block is identified by a 64-bit key that the caller derives from the whole prefix up to and including
+ * that block (a chained hash of its tokens); key 0 marks a block that is never cached (a partly filled
+ * tail) and is freed on release.  A block is found again only through the unbroken chain before it.
+ *
+ * All functions are host functions, touch no device memory and are not thread safe per object.
+ * Status codes are those of glm.h plus GLM_ERR_CACHE_FULL.
+ */
+#ifndef GLM_CACHE_H
+#define GLM_CACHE_H
+
+#include "glm.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GLM_ERR_CACHE_FULL (-9) /* not enough free or evictable blocks; the call changed nothing */
+
+struct glm_cache; /* opaque */
+
+/* num_blocks physical blocks with ids 0 .. num_blocks-1, all free.  NULL + *status on failure. */
+GLM_API struct glm_cache *glm_cache_create(int32_t num_blocks, int *status);
+GLM_API void glm_cache_destroy(struct glm_cache *c);
+
+/*
+ * One call's block table: n blocks with chained keys keys[i] and priorities tiers[i] in 1..4.
+ * Leading blocks whose keys are cached are hits and keep their physical ids (*n_hit_out of them: their K/V
+ * need not be computed again); every other block gets a free id, evicting by the policy if none is free.
+ * All n blocks are referenced until glm_cache_release.  session tags Priority II blocks.
+ *   keys, tiers   host arrays [n];  ids_out host array [n]
+ * Returns GLM_OK, GLM_ERR_NULL, GLM_ERR_RANGE (n < 0, a tier outside 1..4) or GLM_ERR_CACHE_FULL.
+ */
+GLM_API int glm_cache_acquire(struct glm_cache *c, const uint64_t *keys, const uint8_t *tiers, int32_t n, int64_t session,
+                              int32_t *ids_out, int32_t *n_hit_out);
+
+/* Drops one reference from each of the n blocks (the ids one glm_cache_acquire returned, in that order).
+ * Returns GLM_ERR_RANGE if an id is outside the pool or not referenced (nothing is changed then). */
+GLM_API int glm_cache_release(struct glm_cache *c, const int32_t *ids, int32_t n);
+
+/* The session's question is resolved: its Priority II blocks become Priority III. */
+GLM_API int glm_cache_end_session(struct glm_cache *c, int64_t session);
+
+/* Physical id of the cached block with this key, or -1. */
+GLM_API int32_t glm_cache_lookup(const struct glm_cache *c, uint64_t key);
+/* Priority 1..4 of a block that holds data, 0 for a free block, -1 for an id outside the pool. */
+GLM_API int32_t glm_cache_block_tier(const struct glm_cache *c, int32_t id);
+/* Keys of the blocks evicted since the last call of this function, oldest first; returns how many there
+ * were (at most cap are written). */
+GLM_API int32_t glm_cache_drain_evicted(struct glm_cache *c, uint64_t *keys_out, int32_t cap);
+/* out[0] hits, [1] misses, [2] evictions of Priority II, [3] of III, [4] of IV, [5] blocks holding data,
+ * [6] blocks referenced by running calls, [7] num_blocks. */
+GLM_API void glm_cache_stats(const struct glm_cache *c, int64_t out[8]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,146 @@
+"""Test infrastructure: a plain, slow model of the four-tier priority eviction policy for prefix KV-cache
+blocks (paper Sec. 5.3, "Priority-based KV Cache Eviction Policy").  Lists and linear scans only; it shares
+no code with the C++ block manager and must never be imported by the product path.
+
+What the section fixes, in the order it is applied here:
+  * every cached block carries one of four priorities; Priority I (the agents' shared template prefixes)
+    is never evicted;
+  * Priority II belongs to a query session (the reasoning agent's notebook) and is downgraded to
+    Priority III when that session ends;
+  * when no block is free, blocks are evicted Priority IV first, then III, then II, and inside one
+    priority the least recently used block goes first;
+  * identical prefixes reuse their cached blocks (prefix caching, Sec. 2.4): a block is found again only
+    through the unbroken chain of blocks before it.
+Readings of what the section leaves open (kept identical in the C++ manager, listed in the design notes):
+  * a block that a running call still references is not evictable;
+  * "use" time of a block is the moment its last reference is released; the blocks of one call are stamped
+    deepest first, so a chain loses its tail before its head;
+  * a hit under a stronger priority keeps the stronger one (and takes the new session if that is II);
+  * a block key of 0 marks a block that is never cached (a partly filled tail): it is freed on release.
+"""
+from __future__ import annotations
+
+FULL = -9          # not enough evictable blocks
+
+
+class Block:
+    def __init__(self):
+        self.key = 0
+        self.tier = 4
+        self.session = -1
+        self.ref = 0
+        self.stamp = 0
+        self.live = False      # holds data somebody may still want (referenced or cached)
+
+
+class CachePolicy:
+    def __init__(self, num_blocks: int):
+        self.blocks = [Block() for _ in range(num_blocks)]
+        self.by_key = {}
+        self.clock = 0
+        self.hits = 0
+        self.misses = 0
+        self.evictions = {2: 0, 3: 0, 4: 0}
+        self.evicted_keys = []          # in eviction order, for the tests
+
+    # -- helpers
+    def _free_ids(self):
+        return [i for i, b in enumerate(self.blocks) if not b.live]
+
+    def _victim(self):
+        for tier in (4, 3, 2):
+            cand = [i for i, b in enumerate(self.blocks)
+                    if b.live and b.ref == 0 and b.key != 0 and b.tier == tier]
+            if cand:
+                return min(cand, key=lambda i: self.blocks[i].stamp)
+        return None
+
+    def _take_block(self):
+        free = self._free_ids()
+        if free:
+            return free[0]
+        v = self._victim()
+        if v is None:
+            return None
+        b = self.blocks[v]
+        self.evictions[b.tier] += 1
+        self.evicted_keys.append(b.key)
+        if self.by_key.get(b.key) == v:
+            del self.by_key[b.key]
+        b.live = False
+        return v
+
+    # -- operations
+    def acquire(self, keys, tiers, session):
+        """Returns (ids, n_hit) or FULL.  keys[i] is the chained key of block i (0 = never cached).
+        A call that cannot be served changes nothing."""
+        assert len(keys) == len(tiers)
+        # which leading blocks are cached
+        hit_ids = []
+        for k in keys:
+            i = self.by_key.get(k) if k != 0 else None
+            if i is None:
+                break
+            hit_ids.append(i)
+        n_hit = len(hit_ids)
+        need = len(keys) - n_hit
+        free = len(self._free_ids())
+        evictable = sum(1 for i, b in enumerate(self.blocks)
+                        if b.live and b.ref == 0 and b.key != 0 and b.tier >= 2 and i not in hit_ids)
+        if need > free + evictable:
+            return FULL
+        ids = []
+        for j, (k, t) in enumerate(zip(keys, tiers)):
+            if j < n_hit:
+                i = hit_ids[j]
+                b = self.blocks[i]
+                b.ref += 1
+                if t < b.tier:
+                    b.tier = t
+                if b.tier == 2 and t == 2:
+                    b.session = session
+                ids.append(i)
+                continue
+            i = self._take_block()
+            assert i is not None
+            b = self.blocks[i]
+            b.key, b.tier, b.session, b.ref, b.live, b.stamp = k, t, (session if t == 2 else -1), 1, True, 0
+            if k != 0:
+                old = self.by_key.get(k)
+                if old is not None:             # a block of a broken chain under the same key: unreachable now
+                    ob = self.blocks[old]
+                    if ob.ref == 0:
+                        ob.live = False
+                    else:
+                        ob.key = 0
+                self.by_key[k] = i
+            ids.append(i)
+        self.hits += n_hit
+        self.misses += need
+        return ids, n_hit
+
+    def release(self, ids):
+        for i in reversed(ids):             # deepest first: the tail of a chain is the older use
+            b = self.blocks[i]
+            assert b.ref > 0
+            b.ref -= 1
+            if b.ref == 0:
+                if b.key == 0:
+                    b.live = False          # never cached
+                else:
+                    self.clock += 1
+                    b.stamp = self.clock
+
+    def end_session(self, session):
+        for b in self.blocks:
+            if b.live and b.tier == 2 and b.session == session:
+                b.tier = 3
+                b.session = -1
+
+    # -- inspection
+    def resident(self):
+        """key -> tier for every cached (reachable) block."""
+        return {b.key: b.tier for i, b in enumerate(self.blocks) if b.live and b.key != 0 and self.by_key.get(b.key) == i}
+
+    def used(self):
+        return sum(1 for b in self.blocks if b.live)

@@ -28,7 +28,10 @@ EXPORTS = (
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
     "glm_profile_enable", "glm_profile_reset", "glm_profile_read", "glm_bench_mfma", "glm_bench_copy",
+    "glm_cache_create", "glm_cache_destroy", "glm_cache_acquire", "glm_cache_release", "glm_cache_end_session",
+    "glm_cache_lookup", "glm_cache_block_tier", "glm_cache_drain_evicted", "glm_cache_stats",
 )
+GLM_ERR_CACHE_FULL = -9
 KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5}
 
 
@@ -68,6 +71,25 @@ def _load() -> ctypes.CDLL:
     lib.glm_kv_gather.restype = ctypes.c_int
     lib.glm_kv_append.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
     lib.glm_kv_append.restype = ctypes.c_int
+    i64 = ctypes.c_int64
+    lib.glm_cache_create.argtypes = [i32, ctypes.POINTER(ctypes.c_int)]
+    lib.glm_cache_create.restype = vp
+    lib.glm_cache_destroy.argtypes = [vp]
+    lib.glm_cache_destroy.restype = None
+    lib.glm_cache_acquire.argtypes = [vp, vp, vp, i32, i64, vp, ctypes.POINTER(i32)]
+    lib.glm_cache_acquire.restype = ctypes.c_int
+    lib.glm_cache_release.argtypes = [vp, vp, i32]
+    lib.glm_cache_release.restype = ctypes.c_int
+    lib.glm_cache_end_session.argtypes = [vp, i64]
+    lib.glm_cache_end_session.restype = ctypes.c_int
+    lib.glm_cache_lookup.argtypes = [vp, ctypes.c_uint64]
+    lib.glm_cache_lookup.restype = i32
+    lib.glm_cache_block_tier.argtypes = [vp, i32]
+    lib.glm_cache_block_tier.restype = i32
+    lib.glm_cache_drain_evicted.argtypes = [vp, vp, i32]
+    lib.glm_cache_drain_evicted.restype = i32
+    lib.glm_cache_stats.argtypes = [vp, vp]
+    lib.glm_cache_stats.restype = None
     lib.glm_plan_create.argtypes = [glm_geom, vp, i32, vp, vp, i32, vp, ctypes.POINTER(ctypes.c_int)]
     lib.glm_plan_create.restype = vp
     lib.glm_plan_create_host.argtypes = [glm_geom, vp, i32, vp, vp, i32, ctypes.POINTER(ctypes.c_int)]
@@ -291,3 +313,64 @@ def glm_kv_append(g, kv_pool_dev, k_new_dev, v_new_dev, slot_mapping_dev, n_toke
     if check:
         _check(st, "glm_kv_append")
     return st
+
+
+class Cache:
+    """Owner of a glm_cache handle (host-side block manager); methods mirror the C calls of glm_cache.h."""
+
+    def __init__(self, num_blocks: int):
+        st = ctypes.c_int(0)
+        self.handle = _lib.glm_cache_create(num_blocks, ctypes.byref(st))
+        if not self.handle:
+            _check(st.value, "glm_cache_create")
+        self.num_blocks = num_blocks
+
+    def close(self):
+        if self.handle:
+            _lib.glm_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    def acquire(self, keys, tiers, session: int, check: bool = True):
+        """-> (ids int32 array, n_hit), or the status code if check is False and the call failed."""
+        k = np.ascontiguousarray(keys, dtype=np.uint64)
+        t = np.ascontiguousarray(tiers, dtype=np.uint8)
+        assert k.shape == t.shape and k.ndim == 1
+        ids = np.empty(k.shape[0], np.int32)
+        n_hit = ctypes.c_int32(0)
+        st = _lib.glm_cache_acquire(self.handle, k.ctypes.data_as(ctypes.c_void_p), t.ctypes.data_as(ctypes.c_void_p),
+                                    k.shape[0], session, ids.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n_hit))
+        if st != 0:
+            if check:
+                _check(st, "glm_cache_acquire")
+            return st
+        return ids, n_hit.value
+
+    def release(self, ids, check: bool = True) -> int:
+        a = np.ascontiguousarray(ids, dtype=np.int32)
+        st = _lib.glm_cache_release(self.handle, a.ctypes.data_as(ctypes.c_void_p), a.shape[0])
+        if check:
+            _check(st, "glm_cache_release")
+        return st
+
+    def end_session(self, session: int) -> None:
+        _check(_lib.glm_cache_end_session(self.handle, session), "glm_cache_end_session")
+
+    def lookup(self, key: int) -> int:
+        return _lib.glm_cache_lookup(self.handle, key)
+
+    def block_tier(self, block_id: int) -> int:
+        return _lib.glm_cache_block_tier(self.handle, block_id)
+
+    def drain_evicted(self):
+        buf = np.empty(max(1, self.num_blocks * 4), np.uint64)
+        n = _lib.glm_cache_drain_evicted(self.handle, buf.ctypes.data_as(ctypes.c_void_p), buf.shape[0])
+        return buf[:min(n, buf.shape[0])].copy()
+
+    def stats(self) -> dict:
+        out = np.zeros(8, np.int64)
+        _lib.glm_cache_stats(self.handle, out.ctypes.data_as(ctypes.c_void_p))
+        return dict(zip(("hits", "misses", "evicted_II", "evicted_III", "evicted_IV", "used", "referenced", "num_blocks"),
+                        (int(x) for x in out)))

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libglm.so")
-SOURCES = ("glm_attn.hip", "glm_copy.hip", "glm_plan.cpp", "glm_profile.cpp", "glm_microbench.hip")
+SOURCES = ("glm_attn.hip", "glm_copy.hip", "glm_plan.cpp", "glm_profile.cpp", "glm_microbench.hip", "glm_cache.cpp")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          # packed fp32 VALU forms are kept out of the device code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

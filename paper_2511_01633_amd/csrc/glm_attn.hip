@@ -1139,6 +1139,7 @@ const char *glm_status_string(int status) {
         case GLM_ERR_RANGE: return "an id, length or index list is out of range";
         case GLM_ERR_HIP: return "a HIP call failed";
         case GLM_ERR_ALLOC: return "host allocation failed";
+        case -9: return "block cache full: not enough free or evictable blocks";
         default: return "unknown status";
     }
 }

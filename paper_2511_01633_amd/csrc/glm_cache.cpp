@@ -1,0 +1,255 @@
+// Priority-tiered block manager (host only): prefix caching with the four-tier eviction policy of the
+// paper's Sec. 5.3.  Per tier an intrusive list ordered by time of last release (head = least recently
+// used); only unreferenced cached blocks are on a list, Priority I blocks are on none.
+#include "glm_cache.h"
+
+#include <algorithm>
+#include <cstdint>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+namespace {
+
+struct Block {
+    uint64_t key = 0;
+    int64_t session = -1;
+    uint64_t stamp = 0;
+    int32_t ref = 0;
+    int32_t prev = -1, next = -1;   // neighbours on the tier's list
+    uint8_t tier = 0;               // 0 = free
+    bool queued = false;
+};
+
+struct Queue {
+    int32_t head = -1, tail = -1;
+};
+
+}  // namespace
+
+struct glm_cache {
+    std::vector<Block> blocks;
+    std::vector<int32_t> free_ids;              // taken from the back; lowest id first on a fresh pool
+    std::unordered_map<uint64_t, int32_t> by_key;
+    Queue q[5];                                 // [2], [3], [4] used
+    std::vector<uint64_t> evicted;
+    std::vector<int32_t> scratch_hits;
+    uint64_t clock = 0;
+    int64_t n_queued = 0;                       // blocks on the three lists = evictable blocks
+    int64_t hits = 0, misses = 0, evictions[5] = {0, 0, 0, 0, 0};
+
+    void unlink(int32_t i) {
+        Block &b = blocks[i];
+        if (!b.queued) return;
+        Queue &Q = q[b.tier];
+        if (b.prev >= 0) blocks[b.prev].next = b.next; else Q.head = b.next;
+        if (b.next >= 0) blocks[b.next].prev = b.prev; else Q.tail = b.prev;
+        b.prev = b.next = -1;
+        b.queued = false;
+        --n_queued;
+    }
+    // keeps the list ordered by stamp: walks back from the tail (a fresh release lands at the tail at once)
+    void enqueue(int32_t i) {
+        Block &b = blocks[i];
+        if (b.tier < 2) return;
+        Queue &Q = q[b.tier];
+        int32_t after = Q.tail;
+        while (after >= 0 && blocks[after].stamp > b.stamp) after = blocks[after].prev;
+        b.prev = after;
+        b.next = after >= 0 ? blocks[after].next : Q.head;
+        if (b.prev >= 0) blocks[b.prev].next = i; else Q.head = i;
+        if (b.next >= 0) blocks[b.next].prev = i; else Q.tail = i;
+        b.queued = true;
+        ++n_queued;
+    }
+    void make_free(int32_t i) {
+        Block &b = blocks[i];
+        unlink(i);
+        b = Block{};
+        free_ids.push_back(i);
+    }
+    int32_t take_block() {
+        if (!free_ids.empty()) {
+            const int32_t i = free_ids.back();
+            free_ids.pop_back();
+            return i;
+        }
+        for (int t = 4; t >= 2; --t) {
+            const int32_t v = q[t].head;
+            if (v < 0) continue;
+            Block &b = blocks[v];
+            ++evictions[t];
+            evicted.push_back(b.key);
+            auto it = by_key.find(b.key);
+            if (it != by_key.end() && it->second == v) by_key.erase(it);
+            unlink(v);
+            b = Block{};
+            return v;
+        }
+        return -1;
+    }
+};
+
+extern "C" {
+
+glm_cache *glm_cache_create(int32_t num_blocks, int *status) {
+    int st = GLM_OK;
+    glm_cache *c = nullptr;
+    if (num_blocks <= 0) {
+        st = GLM_ERR_GEOM;
+    } else {
+        try {
+            c = new glm_cache();
+            c->blocks.resize((size_t)num_blocks);
+            c->free_ids.reserve((size_t)num_blocks);
+            for (int32_t i = num_blocks - 1; i >= 0; --i) c->free_ids.push_back(i);
+        } catch (...) {
+            delete c;
+            c = nullptr;
+            st = GLM_ERR_ALLOC;
+        }
+    }
+    if (status) *status = st;
+    return c;
+}
+
+void glm_cache_destroy(glm_cache *c) { delete c; }
+
+int glm_cache_acquire(glm_cache *c, const uint64_t *keys, const uint8_t *tiers, int32_t n, int64_t session,
+                      int32_t *ids_out, int32_t *n_hit_out) {
+    if (!c || !n_hit_out || (n > 0 && (!keys || !tiers || !ids_out))) return GLM_ERR_NULL;
+    if (n < 0) return GLM_ERR_RANGE;
+    for (int32_t j = 0; j < n; ++j)
+        if (tiers[j] < 1 || tiers[j] > 4) return GLM_ERR_RANGE;
+    try {
+        // leading blocks that are cached
+        std::vector<int32_t> &hit = c->scratch_hits;
+        hit.clear();
+        for (int32_t j = 0; j < n; ++j) {
+            if (keys[j] == 0) break;
+            auto it = c->by_key.find(keys[j]);
+            if (it == c->by_key.end()) break;
+            hit.push_back(it->second);
+        }
+        const int32_t n_hit = (int32_t)hit.size();
+        const int64_t need = n - n_hit;
+        int64_t queued_hits = 0;
+        for (int32_t i : hit) queued_hits += c->blocks[i].queued ? 1 : 0;
+        if (need > (int64_t)c->free_ids.size() + c->n_queued - queued_hits) return GLM_ERR_CACHE_FULL;
+        c->by_key.reserve(c->by_key.size() + (size_t)need);
+        c->evicted.reserve(c->evicted.size() + (size_t)need);
+        for (int32_t j = 0; j < n; ++j) {
+            if (j < n_hit) {
+                const int32_t i = hit[j];
+                Block &b = c->blocks[i];
+                c->unlink(i);                    // referenced blocks are on no list
+                ++b.ref;
+                if (tiers[j] < b.tier) b.tier = tiers[j];
+                if (b.tier == 2 && tiers[j] == 2) b.session = session;
+                ids_out[j] = i;
+                continue;
+            }
+            const int32_t i = c->take_block();   // cannot fail: counted above
+            Block &b = c->blocks[i];
+            b.key = keys[j];
+            b.tier = tiers[j];
+            b.session = tiers[j] == 2 ? session : -1;
+            b.ref = 1;
+            b.stamp = 0;
+            if (keys[j] != 0) {
+                auto it = c->by_key.find(keys[j]);
+                if (it != c->by_key.end()) {     // a block of a broken chain under the same key: unreachable now
+                    const int32_t old = it->second;
+                    if (c->blocks[old].ref == 0) c->make_free(old);
+                    else c->blocks[old].key = 0;
+                    it->second = i;
+                } else {
+                    c->by_key.emplace(keys[j], i);
+                }
+            }
+            ids_out[j] = i;
+        }
+        c->hits += n_hit;
+        c->misses += need;
+        *n_hit_out = n_hit;
+    } catch (const std::bad_alloc &) {
+        return GLM_ERR_ALLOC;
+    }
+    return GLM_OK;
+}
+
+int glm_cache_release(glm_cache *c, const int32_t *ids, int32_t n) {
+    if (!c || (n > 0 && !ids)) return GLM_ERR_NULL;
+    if (n < 0) return GLM_ERR_RANGE;
+    const int32_t N = (int32_t)c->blocks.size();
+    // an id may occur several times in one list only as often as it is referenced
+    try {
+        std::vector<int32_t> sorted(ids, ids + n);
+        std::sort(sorted.begin(), sorted.end());
+        for (int32_t j = 0; j < n;) {
+            const int32_t id = sorted[j];
+            int32_t k = j;
+            while (k < n && sorted[k] == id) ++k;
+            if (id < 0 || id >= N || c->blocks[id].ref < k - j) return GLM_ERR_RANGE;
+            j = k;
+        }
+    } catch (const std::bad_alloc &) {
+        return GLM_ERR_ALLOC;
+    }
+    for (int32_t j = n - 1; j >= 0; --j) {       // deepest first: the tail of a chain is the older use
+        const int32_t i = ids[j];
+        Block &b = c->blocks[i];
+        if (--b.ref > 0) continue;
+        if (b.key == 0) {
+            c->make_free(i);                      // never cached
+        } else {
+            b.stamp = ++c->clock;
+            c->enqueue(i);
+        }
+    }
+    return GLM_OK;
+}
+
+int glm_cache_end_session(glm_cache *c, int64_t session) {
+    if (!c) return GLM_ERR_NULL;
+    for (int32_t i = 0; i < (int32_t)c->blocks.size(); ++i) {
+        Block &b = c->blocks[i];
+        if (b.tier != 2 || b.session != session) continue;
+        const bool was_queued = b.queued;
+        c->unlink(i);
+        b.tier = 3;
+        b.session = -1;
+        if (was_queued) c->enqueue(i);            // keeps its time of use
+    }
+    return GLM_OK;
+}
+
+int32_t glm_cache_lookup(const glm_cache *c, uint64_t key) {
+    if (!c || key == 0) return -1;
+    auto it = c->by_key.find(key);
+    return it == c->by_key.end() ? -1 : it->second;
+}
+
+int32_t glm_cache_block_tier(const glm_cache *c, int32_t id) {
+    if (!c || id < 0 || id >= (int32_t)c->blocks.size()) return -1;
+    return c->blocks[id].tier;
+}
+
+int32_t glm_cache_drain_evicted(glm_cache *c, uint64_t *keys_out, int32_t cap) {
+    if (!c) return 0;
+    const int32_t n = (int32_t)c->evicted.size();
+    for (int32_t i = 0; i < n && i < cap && keys_out; ++i) keys_out[i] = c->evicted[i];
+    c->evicted.clear();
+    return n;
+}
+
+void glm_cache_stats(const glm_cache *c, int64_t out[8]) {
+    if (!c || !out) return;
+    int64_t used = 0, refd = 0;
+    for (const Block &b : c->blocks) { used += b.tier != 0; refd += b.ref > 0; }
+    out[0] = c->hits; out[1] = c->misses;
+    out[2] = c->evictions[2]; out[3] = c->evictions[3]; out[4] = c->evictions[4];
+    out[5] = used; out[6] = refd; out[7] = (int64_t)c->blocks.size();
+}
+
+}  // extern "C"

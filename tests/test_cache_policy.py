@@ -1,0 +1,256 @@
+"""Block manager (priority-tiered prefix cache): the policy oracle against what the paper's case study and the
+policy's own rules fix, then the C++ manager against the oracle.  CPU only."""
+import json
+import os
+import zlib
+
+import numpy as np
+import pytest
+
+import paper_2511_01633_amd as glm
+from oracle.cache_policy import FULL, CachePolicy
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def chain_keys(names):
+    """Chained key of block i = a hash of the names of blocks 0..i (never 0)."""
+    out, acc = [], b""
+    for n in names:
+        acc += b"/" + n.encode()
+        out.append((zlib.crc32(acc) | (zlib.adler32(acc) << 32)) or 1)
+    return out
+
+
+class OracleSide:
+    def __init__(self, n):
+        self.c = CachePolicy(n)
+
+    def call(self, keys, tiers, session):
+        r = self.c.acquire(keys, tiers, session)
+        if r == FULL:
+            return None
+        ids, n_hit = r
+        return list(ids), n_hit
+
+    def release(self, ids):
+        self.c.release(ids)
+
+    def end(self, s):
+        self.c.end_session(s)
+
+    def resident(self):
+        return self.c.resident()
+
+    def drain(self):
+        e = list(self.c.evicted_keys)
+        self.c.evicted_keys.clear()
+        return e
+
+    def tier_of_id(self, i):
+        b = self.c.blocks[i]
+        return b.tier if b.live else 0
+
+
+class NativeSide:
+    def __init__(self, n):
+        self.c = glm.Cache(n)
+        self.keys_seen = set()
+
+    def call(self, keys, tiers, session):
+        self.keys_seen.update(k for k in keys if k)
+        r = self.c.acquire(keys, tiers, session, check=False)
+        if isinstance(r, int):
+            assert r == glm.GLM_ERR_CACHE_FULL
+            return None
+        return [int(x) for x in r[0]], r[1]
+
+    def release(self, ids):
+        self.c.release(ids)
+
+    def end(self, s):
+        self.c.end_session(s)
+
+    def resident(self):
+        out = {}
+        for k in self.keys_seen:
+            i = self.c.lookup(k)
+            if i >= 0:
+                out[k] = self.c.block_tier(i)
+        return out
+
+    def drain(self):
+        return [int(k) for k in self.c.drain_evicted()]
+
+    def tier_of_id(self, i):
+        return self.c.block_tier(i)
+
+
+@pytest.mark.parametrize("side", [OracleSide, NativeSide], ids=["oracle", "native"])
+def test_case_study_of_the_paper(side):
+    """Sec. 5.3 case study: every step's evictions, survivors, downgrades and reinsertions."""
+    fx = json.load(open(os.path.join(HERE, "golden", "fig8_case_study.json")))
+    m = side(fx["num_blocks"])
+    name_of = {}
+    for st in fx["steps"]:
+        hits = []
+        for op in st["ops"]:
+            if op[0] == "end":
+                m.end(op[1])
+                continue
+            _, names, tiers, session = op
+            keys = chain_keys(names)
+            for k, nm in zip(keys, names):
+                name_of[k] = nm
+            r = m.call(keys, tiers, session)
+            assert r is not None, (st["step"], names)
+            ids, n_hit = r
+            hits.append(n_hit)
+            m.release(ids)
+        if "hits" in st:
+            assert hits == st["hits"], st["step"]
+        assert sorted(name_of[k] for k in m.drain()) == sorted(st["evicted"]), st["step"]
+        assert {name_of[k]: t for k, t in m.resident().items()} == st["resident"], st["step"]
+
+
+def _oracle_rules_trace(seed, n_blocks=24, n_ops=400):
+    """Random calls over a small vocabulary of chains; yields (op, args) and lets the caller check."""
+    rng = np.random.default_rng(seed)
+    prefixes = ["PC", "PR", "PA"]
+    ops = []
+    open_calls = []
+    for _ in range(n_ops):
+        r = rng.random()
+        if r < 0.55 or not open_calls:
+            p = prefixes[rng.integers(3)]
+            sess = int(rng.integers(1, 6))
+            names, tiers = [p], [1]
+            if p == "PR":
+                for f in range(int(rng.integers(0, 4))):
+                    names.append("s%d.fact%d" % (sess, f)); tiers.append(2)
+            for q in range(int(rng.integers(0, 4))):
+                names.append("q%d.%d" % (int(rng.integers(0, 12)), q)); tiers.append(4)
+            keys = chain_keys(names)
+            if rng.random() < 0.3:
+                keys.append(0); tiers.append(4)          # a partly filled tail block, never cached
+            ops.append(("call", keys, tiers, sess))
+            open_calls.append(len(ops) - 1)
+        elif r < 0.9:
+            j = open_calls.pop(int(rng.integers(len(open_calls))))
+            ops.append(("release", j))
+        else:
+            ops.append(("end", int(rng.integers(1, 6))))
+    return ops
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_oracle_obeys_the_policy_rules(seed):
+    """What Sec. 5.3 fixes, checked on the oracle without using its own bookkeeping for the verdict:
+    Priority I is never evicted; a victim is never referenced; a victim's priority is the weakest one that has an
+    unreferenced cached block, and it is the least recently released block of that priority."""
+    n_blocks = 24
+    o = CachePolicy(n_blocks)
+    held = {}                      # op index -> ids
+    tier_of, last_release, refcount = {}, {}, {}
+    clock = 0
+    for idx, op in enumerate(_oracle_rules_trace(seed, n_blocks)):
+        if op[0] == "call":
+            _, keys, tiers, sess = op
+            before = dict(o.resident())
+            r = o.acquire(keys, tiers, sess)
+            evicted = list(o.evicted_keys); o.evicted_keys.clear()
+            if r == FULL:
+                assert o.resident() == before
+                continue
+            ids, n_hit = r
+            assert len(set(ids)) == len(ids)
+            for k in evicted:
+                assert tier_of[k] != 1, "Priority I evicted"
+                assert refcount.get(k, 0) == 0, "referenced block evicted"
+            # replay the victims one by one against the shadow bookkeeping
+            shadow = {k: (tier_of[k], last_release[k]) for k in before if refcount.get(k, 0) == 0 and tier_of[k] >= 2
+                      and k not in keys[:n_hit]}
+            for k in evicted:
+                weakest = max(t for t, _ in shadow.values())
+                assert shadow[k][0] == weakest, "a stronger priority was evicted first"
+                assert shadow[k][1] == min(s for t, s in shadow.values() if t == weakest), "not the least recently used"
+                del shadow[k]
+            for k in evicted:
+                tier_of.pop(k, None); last_release.pop(k, None)
+            for j, (k, t) in enumerate(zip(keys, tiers)):
+                if k == 0:
+                    continue
+                tier_of[k] = min(t, tier_of[k]) if (j < n_hit and k in tier_of) else t
+                refcount[k] = refcount.get(k, 0) + 1
+            held[idx] = (ids, keys)
+            assert o.used() <= n_blocks
+        elif op[0] == "release":
+            if op[1] not in held:
+                continue
+            ids, keys = held.pop(op[1])
+            o.release(ids)
+            for k in reversed(keys):
+                if k == 0:
+                    continue
+                refcount[k] -= 1
+                if refcount[k] == 0:
+                    clock += 1
+                    last_release[k] = clock
+        else:
+            o.end_session(op[1])
+            # the oracle's view of tiers is the reference for downgrades: II -> III only, for that session only
+            for k, t in o.resident().items():
+                if tier_of.get(k) == 2 and t == 3:
+                    tier_of[k] = 3
+        for k, t in o.resident().items():
+            assert tier_of[k] == t
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_native_manager_follows_the_oracle(seed):
+    n_blocks = 24
+    o, n = OracleSide(n_blocks), NativeSide(n_blocks)
+    held = {}
+    for idx, op in enumerate(_oracle_rules_trace(seed, n_blocks, 600)):
+        if op[0] == "call":
+            _, keys, tiers, sess = op
+            ro, rn = o.call(keys, tiers, sess), n.call(keys, tiers, sess)
+            assert (ro is None) == (rn is None), idx
+            if ro is None:
+                continue
+            assert ro[1] == rn[1], idx                       # same number of hits
+            assert len(set(rn[0])) == len(rn[0])
+            assert all(0 <= i < n_blocks for i in rn[0])
+            held[idx] = (ro[0], rn[0])
+        elif op[0] == "release":
+            if op[1] in held:
+                a, b = held.pop(op[1])
+                o.release(a); n.release(b)
+        else:
+            o.end(op[1]); n.end(op[1])
+        assert o.drain() == n.drain(), idx                   # same victims in the same order
+        assert o.resident() == n.resident(), idx             # same cached keys with the same priorities
+        # blocks referenced by open calls are disjoint from free blocks and never handed out twice
+        live = [i for _, ids in held.values() for i in ids]
+        for i in live:
+            assert n.tier_of_id(i) >= 1
+    st = n.c.stats()
+    assert st["hits"] == o.c.hits and st["misses"] == o.c.misses
+    assert (st["evicted_II"], st["evicted_III"], st["evicted_IV"]) == (o.c.evictions[2], o.c.evictions[3], o.c.evictions[4])
+
+
+def test_native_argument_errors():
+    c = glm.Cache(4)
+    ids, n_hit = c.acquire(chain_keys(["a", "b"]), [1, 4], 0)
+    assert n_hit == 0 and sorted(ids) == [0, 1]
+    assert c.acquire(chain_keys(["x"]), [5], 0, check=False) == glm.GLM_ERR_RANGE
+    assert c.release([7], check=False) == glm.GLM_ERR_RANGE
+    assert c.release([int(ids[0]), int(ids[0])], check=False) == glm.GLM_ERR_RANGE      # referenced once only
+    c.release(ids)
+    assert c.release(ids, check=False) == glm.GLM_ERR_RANGE                               # no reference left
+    # a pool whose blocks are all pinned or referenced cannot serve more
+    a = c.acquire(chain_keys(["p1", "p2", "p3"]), [1, 1, 1], 0)
+    assert c.acquire(chain_keys(["q1", "q2"]), [4, 4], 0, check=False) == glm.GLM_ERR_CACHE_FULL
+    assert c.stats()["used"] == 4                                                         # a, p1..p3 ("b" was evicted)
+    with pytest.raises(Exception):
+        glm.Cache(0)

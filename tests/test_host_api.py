@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "glm.h")).read()
+    header = open(os.path.join(ROOT, "include", "glm.h")).read() + open(os.path.join(ROOT, "include", "glm_cache.h")).read()
     declared = set(re.findall(r"GLM_API[^;(]*?\b(glm_[a-z_0-9]+)\s*\(", header))
     assert declared == set(glm.EXPORTS), declared ^ set(glm.EXPORTS)
     lib = ctypes.CDLL(glm.LIB_PATH)

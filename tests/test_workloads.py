@@ -71,3 +71,17 @@ def test_churn_step_lists_are_consistent():
     assert len(set(st.readmit_ids.tolist())) == st.readmit_ids.size == st.evict_ids.size
     assert ((st.fork_ntok >= 1) & (st.fork_ntok <= 16)).all()
     assert not (set(st.evict_ids.tolist()) & set(st.block_tables[st.block_tables >= 0].tolist()))
+
+
+def test_agent_trace_is_seeded_and_well_formed():
+    a = list(W.agent_trace(n_sessions=6, concurrency=3))
+    b = list(W.agent_trace(n_sessions=6, concurrency=3))
+    assert a == b
+    ended = [op[1] for op in a if op[0] == "end"]
+    assert sorted(ended) == list(range(6))
+    for op in a:
+        if op[0] == "call":
+            _, names, tiers, sess = op
+            assert len(names) == len(tiers) and set(tiers) <= {1, 2, 4}
+            assert tiers == sorted(tiers)[:len(tiers)] or tiers[-1] == 4      # prefix (I), notebook (II), question (IV)
+            assert names[0].startswith("P") and sess not in ended[:0]

@@ -25,6 +25,7 @@ from .gen import (  # noqa: F401
     tree_decode_70b,
     eviction_churn,
     churn_step,
+    agent_trace,
     new_token_slots,
     custom_decode,
     custom_prefill,

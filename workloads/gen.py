@@ -451,3 +451,48 @@ def new_token_slots(w: Workload) -> np.ndarray:
 
 def make_config(index: int, seed: Optional[int] = None) -> Workload:
     return (tiny_decode, llama8b_decode, prefill_on_prefix, tree_decode_70b, eviction_churn)[index](seed)
+
+
+def agent_trace(seed: int = 20251106, n_sessions: int = 64, concurrency: int = 8, prefix_blocks: int = 8,
+                question_blocks: int = 2, fact_blocks: int = 3, max_rounds: int = 4, vertex_pool: int = 48):
+    """Synthetic stand-in for the call sequence of the paper's three-agent serving loop (Sec. 4, 5.2, 5.3): each
+    question is classified once (C-Agent: template prefix + question), then alternates reasoning calls (R-Agent:
+    template prefix + notebook + question) and action calls (A-Agent: template prefix + missing-information
+    request), the notebook growing by one retrieved vertex chunk per round; vertex chunks are drawn from a small
+    pool with a skewed distribution, so different questions meet the same chunk.  `concurrency` questions are in
+    flight, their calls interleaved round-robin.
+    Yields ("call", names, tiers, session) and ("end", session); names are block names whose chained hash is the
+    block key, tiers follow Sec. 5.3 (I template prefix, II notebook, IV question / request)."""
+    rng = _rng(seed)
+    weights = 1.0 / np.arange(1, vertex_pool + 1)
+    weights /= weights.sum()
+
+    def blocks(tag, n):
+        return ["%s.%d" % (tag, i) for i in range(n)]
+
+    def session(s):
+        q = blocks("q%d" % s, question_blocks)
+        yield ("call", blocks("PC", prefix_blocks) + q, [1] * prefix_blocks + [4] * question_blocks, s)
+        notebook = []
+        for rnd in range(int(rng.integers(1, max_rounds + 1))):
+            yield ("call", blocks("PR", prefix_blocks) + notebook + q,
+                   [1] * prefix_blocks + [2] * len(notebook) + [4] * question_blocks, s)
+            v = int(rng.choice(vertex_pool, p=weights))
+            yield ("call", blocks("PA", prefix_blocks) + blocks("m%d.%d" % (s, rnd), question_blocks),
+                   [1] * prefix_blocks + [4] * question_blocks, s)
+            # facts are kept in a canonical (sorted) order so that equal notebooks give equal prefixes
+            notebook = sorted(set(notebook + blocks("v%d" % v, fact_blocks)))
+        yield ("call", blocks("PR", prefix_blocks) + notebook + q,
+               [1] * prefix_blocks + [2] * len(notebook) + [4] * question_blocks, s)
+        yield ("end", s)
+
+    pending = [session(s) for s in range(n_sessions)]
+    active = []
+    while pending or active:
+        while pending and len(active) < concurrency:
+            active.append(pending.pop(0))
+        for gen in list(active):
+            try:
+                yield next(gen)
+            except StopIteration:
+                active.remove(gen)
