@@ -20,6 +20,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -33,7 +35,7 @@ def _parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
-    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn (default all)")
+    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3 (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-headline", action="store_true",
                     help="profiling aid: run only the workloads named by --only and print their records")
@@ -227,6 +229,25 @@ def bench_churn(glm, W, w, steps, warmup, variants=4):
     return res
 
 
+def bench_gather_tokens(glm, w, steps, warmup):
+    """Every request of the batch made dense through its block table (shared prefixes are copied once per branch)."""
+    import torch
+    g = w.geom
+    pool, tables, lens = _dev(w.pool), _dev(w.block_tables), _dev(w.seq_lens)
+    per_tok = 2 * g.num_kv_heads * g.head_dim
+    offs = np.concatenate([[0], np.cumsum(w.seq_lens.astype(np.int64) * per_tok)])
+    dst = torch.empty(int(offs[-1]), dtype=torch.int16, device="cuda")
+    offs_d = torch.from_numpy(offs[:-1].copy()).cuda()
+    mx = int(w.seq_lens.max())
+
+    def step(i):
+        glm.glm_kv_gather_tokens(g, pool, tables, w.max_blocks, lens, offs_d, w.B, mx, dst)
+
+    ms = _time_steps(step, steps, warmup)
+    nbytes = 2 * int(offs[-1]) * 2
+    return {"workload": w.name, "ms": ms, "bytes_read_plus_written": nbytes, "GBps": nbytes / ms / 1e6}
+
+
 def bench_cache_policy(glm, W):
     """Host-side block manager on a synthetic three-agent call trace: block hit rate of the four-tier policy against
     one LRU queue for everything (same manager, every block Priority IV), and calls per second."""
@@ -320,10 +341,11 @@ def main():
         sys.exit(1)
     import paper_2511_01633_amd as glm
     import workloads as W
-    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn"}
+    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3"}
     torch.cuda.set_device(0)
     extra = {}
-    if args.skip_headline:
+
+    def run_extras():
         if "prefill" in only:
             extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(5, args.steps // 4), max(2, args.warmup // 4))
         if "tree70b" in only:
@@ -331,6 +353,14 @@ def main():
                                                     max(2, args.warmup // 4))
         if "churn" in only:
             extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+        if "qwen3" in only:
+            extra["qwen3_moe_decode"] = bench_decode(glm, W.qwen3_moe_decode(), args.layers, max(10, args.steps // 2),
+                                                     max(2, args.warmup // 2))
+            extra["kv_gather_tokens"] = bench_gather_tokens(glm, W.llama8b_decode(), max(10, args.steps // 4), 4)
+        extra["cache_policy"] = bench_cache_policy(glm, W)
+
+    if args.skip_headline:
+        run_extras()
         print(json.dumps({"reference_rates": reference_rates(glm), "extra": extra}))
         return
 
@@ -351,14 +381,7 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w2, w2.unique_kv_bytes() + w2.q.nbytes + w2.B * w2.geom.num_q_heads * w2.geom.head_dim * 4)
     del w2
-    if "prefill" in only:
-        extra["prefill_on_prefix"] = bench_prefill(glm, W.prefill_on_prefix(), max(5, args.steps // 4), max(2, args.warmup // 4))
-    if "tree70b" in only:
-        extra["tree_decode_70b"] = bench_decode(glm, W.tree_decode_70b(), min(args.layers, 16), max(10, args.steps // 4),
-                                                max(2, args.warmup // 4))
-    if "churn" in only:
-        extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
-    extra["cache_policy"] = bench_cache_policy(glm, W)
+    run_extras()
     line["reference_rates"] = reference_rates(glm)
     line["extra"] = extra
     print(json.dumps(line))

@@ -149,6 +149,20 @@ GLM_API int glm_kv_append(glm_geom g, void *kv_pool_dev, const void *k_new_dev, 
                           const int64_t *slot_mapping_dev, int32_t n_tokens, void *hip_stream);
 
 /*
+ * Token-granular gather (the paged cache of Sec. 2.4 made dense again, e.g. to hand a request's cached K/V to
+ * a recovery or debugging path): request r's tokens 0 .. seq_lens[r]-1, read through its block table, are
+ * written contiguously as [2 (K,V)][Hkv][seq_lens[r]][d] bf16 starting at element dst_offsets[r] of dst.
+ * Preconditions (GLM_VALIDATE=1 -> GLM_ERR_RANGE): table entries of visible blocks inside the pool,
+ * seq_lens[r] <= max_blocks * block_size; dst_offsets multiples of 8 elements, slabs disjoint and inside dst
+ * (not checked).  B == 0 returns GLM_OK without a launch.
+ *   block_tables_dev  int32 [B][max_blocks];  seq_lens_dev int32 [B];  dst_offsets_dev int64 [B]
+ *   max_seq_len       upper bound of seq_lens (sizes the launch)
+ */
+GLM_API int glm_kv_gather_tokens(glm_geom g, const void *kv_pool_dev, const int32_t *block_tables_dev, int32_t max_blocks,
+                                 const int32_t *seq_lens_dev, const int64_t *dst_offsets_dev, int32_t B, int32_t max_seq_len,
+                                 void *dst_dev, void *hip_stream);
+
+/*
  * Plan: derived on the host from the block tables.  Maximal runs of logical blocks that the
  * same set of requests reference through identical physical ids become shared segments
  * (a prefix tree: agent template -> graph context -> private suffix, paper Sec. 5.2); the plan
@@ -200,7 +214,8 @@ GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing H
  * is bracketed by two HIP events recorded on the stream it is launched on.  glm_profile_read
  * waits for the recorded events of one kernel kind and returns their summed duration and count
  * since the last glm_profile_reset.  Kernel ids: 0 wave-private streaming attention kernel,
- * 1 cooperative attention kernel, 2 split-K merge, 3 gather, 4 fork copy, 5 K/V append.
+ * 1 cooperative attention kernel, 2 split-K merge, 3 gather, 4 fork copy, 5 K/V append,
+ * 6 token gather.
  * Disabled by default; enabling it adds event records between kernels, so whole-call timings
  * should be taken with it off.
  */

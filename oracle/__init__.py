@@ -10,5 +10,6 @@ from .loader import (  # noqa: F401
     fork_copy,
     gather,
     kv_append,
+    gather_tokens,
     lib_path,
 )

@@ -254,3 +254,25 @@ int glm_oracle_kv_append(oracle_geom g, uint16_t *pool, const uint16_t *k_new, c
     }
     return 0;
 }
+
+/* Token-granular gather: request r's cached tokens 0 .. seq_lens[r]-1, read through its block table, are laid
+ * out contiguously as [2 (K,V)][Hkv][seq_lens[r]][d] starting at element dst_offsets[r] of dst (the cache of
+ * Sec. 2.4 made dense again: what a paged request "really" holds). */
+int glm_oracle_gather_tokens(oracle_geom g, const uint16_t *pool, const int32_t *tables, int32_t max_blocks,
+                             const int32_t *seq_lens, const int64_t *dst_offsets, int32_t B, uint16_t *dst) {
+    if (check_geom(&g)) return -1;
+    const int64_t d = g.head_dim, bs = g.block_size, Hkv = g.num_kv_heads;
+    for (int r = 0; r < B; ++r) {
+        const int64_t L = seq_lens[r];
+        if (L < 0 || L > (int64_t)max_blocks * bs) return -2;
+        for (int p = 0; p < 2; ++p)
+            for (int h = 0; h < Hkv; ++h)
+                for (int64_t j = 0; j < L; ++j) {
+                    const int64_t blk = tables[(int64_t)r * max_blocks + j / bs], t = j % bs;
+                    if (blk < 0 || blk >= g.num_blocks) return -3;
+                    for (int c = 0; c < d; ++c)
+                        dst[dst_offsets[r] + ((p * Hkv + h) * L + j) * d + c] = pool[((((blk * 2 + p) * Hkv + h) * bs + t) * d) + c];
+                }
+    }
+    return 0;
+}

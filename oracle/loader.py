@@ -138,3 +138,17 @@ def kv_append(geom, pool, k_new, v_new, slots) -> None:
                                       sl.ctypes.data_as(ctypes.c_void_p), ctypes.c_int32(sl.shape[0]))
     if st:
         raise RuntimeError("oracle kv_append failed: %d" % st)
+
+
+def gather_tokens(geom, pool, block_tables, seq_lens, dst_offsets, dst) -> None:
+    """In place on `dst` (uint16, flat): request r's tokens as [2, Hkv, seq_lens[r], d] at element dst_offsets[r]."""
+    tb = np.ascontiguousarray(block_tables, dtype=np.int32)
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    off = np.ascontiguousarray(dst_offsets, dtype=np.int64)
+    pool = np.ascontiguousarray(pool)
+    assert dst.dtype == np.uint16 and dst.flags["C_CONTIGUOUS"]
+    st = _load().glm_oracle_gather_tokens(_geom(geom), _p(pool, np.uint16), _p(tb, np.int32), ctypes.c_int32(tb.shape[1]),
+                                          _p(sl, np.int32), off.ctypes.data_as(ctypes.c_void_p), ctypes.c_int32(sl.shape[0]),
+                                          _p(dst, np.uint16))
+    if st:
+        raise RuntimeError("oracle gather_tokens failed: %d" % st)

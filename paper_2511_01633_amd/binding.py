@@ -22,7 +22,7 @@ GLM_ERR_NULL, GLM_ERR_GEOM, GLM_ERR_ALIGN, GLM_ERR_WORKSPACE = -1, -2, -3, -4
 GLM_ERR_PLAN_MISMATCH, GLM_ERR_RANGE, GLM_ERR_HIP, GLM_ERR_ALLOC = -5, -6, -7, -8
 
 EXPORTS = (
-    "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather", "glm_kv_append",
+    "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather", "glm_kv_append", "glm_kv_gather_tokens",
     "glm_plan_create", "glm_plan_create_host", "glm_plan_destroy", "glm_plan_workspace_bytes",
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
@@ -32,7 +32,7 @@ EXPORTS = (
     "glm_cache_lookup", "glm_cache_block_tier", "glm_cache_drain_evicted", "glm_cache_stats",
 )
 GLM_ERR_CACHE_FULL = -9
-KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5}
+KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5, "kv_gather_tokens": 6}
 
 
 class glm_geom(ctypes.Structure):
@@ -71,6 +71,8 @@ def _load() -> ctypes.CDLL:
     lib.glm_kv_gather.restype = ctypes.c_int
     lib.glm_kv_append.argtypes = [glm_geom, vp, vp, vp, vp, i32, vp]
     lib.glm_kv_append.restype = ctypes.c_int
+    lib.glm_kv_gather_tokens.argtypes = [glm_geom, vp, vp, i32, vp, vp, i32, i32, vp, vp]
+    lib.glm_kv_gather_tokens.restype = ctypes.c_int
     i64 = ctypes.c_int64
     lib.glm_cache_create.argtypes = [i32, ctypes.POINTER(ctypes.c_int)]
     lib.glm_cache_create.restype = vp
@@ -312,6 +314,15 @@ def glm_kv_append(g, kv_pool_dev, k_new_dev, v_new_dev, slot_mapping_dev, n_toke
                             n_tokens, _stream(hip_stream))
     if check:
         _check(st, "glm_kv_append")
+    return st
+
+
+def glm_kv_gather_tokens(g, kv_pool_dev, block_tables_dev, max_blocks: int, seq_lens_dev, dst_offsets_dev, B: int,
+                         max_seq_len: int, dst_dev, hip_stream=None, check: bool = True) -> int:
+    st = _lib.glm_kv_gather_tokens(geom(g), _dev(kv_pool_dev), _dev(block_tables_dev), max_blocks, _dev(seq_lens_dev),
+                                   _dev(dst_offsets_dev), B, max_seq_len, _dev(dst_dev), _stream(hip_stream))
+    if check:
+        _check(st, "glm_kv_gather_tokens")
     return st
 
 

@@ -74,6 +74,28 @@ __global__ void __launch_bounds__(kCopyThreads) append_kernel(u32x4 *__restrict_
     }
 }
 
+// grid = (ceil(max_seq_len / 16), B): one workgroup moves one logical block of one request; a (plane, head) slab
+// of n rows is contiguous both in the block and in the request's dense [2][Hkv][L][d] slab.
+__global__ void __launch_bounds__(kCopyThreads) gather_tokens_kernel(const u32x4 *__restrict__ pool, const int32_t *__restrict__ tables,
+                                                                     const int32_t *__restrict__ seq_lens,
+                                                                     const int64_t *__restrict__ dst_offsets, u32x4 *__restrict__ dst,
+                                                                     int max_blocks, int hkv, int row_pieces, int num_blocks) {
+    const int r = blockIdx.y, b = blockIdx.x;
+    const int64_t L = min(max(seq_lens[r], 0), max_blocks * kBlockSize);
+    const int rows = (int)min((int64_t)kBlockSize, L - (int64_t)b * kBlockSize);
+    if (rows <= 0) return;
+    const int id = min(max(tables[(int64_t)r * max_blocks + b], 0), num_blocks - 1);     // never reads outside the pool
+    const int slab = kBlockSize * row_pieces;                       // pieces of one (plane, head) slab of a block
+    const u32x4 *sp = pool + (int64_t)id * 2 * hkv * slab;
+    u32x4 *dp = dst + dst_offsets[r] / 8;
+    const int n = rows * row_pieces;
+    for (int ph = 0; ph < 2 * hkv; ++ph) {
+        u32x4 *d = dp + ((int64_t)ph * L + (int64_t)b * kBlockSize) * row_pieces;
+        const u32x4 *sph = sp + (int64_t)ph * slab;
+        for (int p = threadIdx.x; p < n; p += kCopyThreads) d[p] = sph[p];
+    }
+}
+
 namespace {
 
 int validate_ids(const int32_t *ids_dev, int32_t n, int64_t upper, bool distinct, std::vector<int32_t> *keep,
@@ -199,6 +221,46 @@ extern "C" int glm_kv_append(glm_geom g, void *kv_pool_dev, const void *k_new_de
     hipLaunchKernelGGL(append_kernel, dim3(n_tokens), dim3(kCopyThreads), 0, st, (u32x4 *)kv_pool_dev,
                        (const u32x4 *)k_new_dev, (const u32x4 *)v_new_dev, slot_mapping_dev, g.num_kv_heads, row_pieces,
                        pieces, num_slots);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+extern "C" int glm_kv_gather_tokens(glm_geom g, const void *kv_pool_dev, const int32_t *block_tables_dev, int32_t max_blocks,
+                                    const int32_t *seq_lens_dev, const int64_t *dst_offsets_dev, int32_t B, int32_t max_seq_len,
+                                    void *dst_dev, void *hip_stream) {
+    if (int st = check_geom(g)) return st;
+    if (B < 0 || max_blocks <= 0 || max_seq_len < 0) return GLM_ERR_GEOM;
+    if (B == 0 || max_seq_len == 0) return GLM_OK;
+    if (!kv_pool_dev || !block_tables_dev || !seq_lens_dev || !dst_offsets_dev || !dst_dev) return GLM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(kv_pool_dev) | reinterpret_cast<uintptr_t>(dst_dev)) & 15u) return GLM_ERR_ALIGN;
+    if (B > 65535) return GLM_ERR_GEOM;                       // grid.y
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (validate_enabled()) {
+        try {
+            std::vector<int32_t> lens(B), tab((size_t)B * max_blocks);
+            std::vector<int64_t> offs(B);
+            hipError_t e = hipStreamSynchronize(st);
+            if (e == hipSuccess) e = hipMemcpy(lens.data(), seq_lens_dev, (size_t)B * 4, hipMemcpyDeviceToHost);
+            if (e == hipSuccess) e = hipMemcpy(tab.data(), block_tables_dev, tab.size() * 4, hipMemcpyDeviceToHost);
+            if (e == hipSuccess) e = hipMemcpy(offs.data(), dst_offsets_dev, (size_t)B * 8, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return set_hip_error(e);
+            for (int32_t r = 0; r < B; ++r) {
+                if (lens[r] < 0 || lens[r] > max_seq_len || (int64_t)lens[r] > (int64_t)max_blocks * g.block_size) return GLM_ERR_RANGE;
+                if (offs[r] < 0 || (offs[r] & 7)) return GLM_ERR_RANGE;
+                for (int32_t b = 0; b < (lens[r] + g.block_size - 1) / g.block_size; ++b) {
+                    const int32_t id = tab[(size_t)r * max_blocks + b];
+                    if (id < 0 || id >= g.num_blocks) return GLM_ERR_RANGE;
+                }
+            }
+        } catch (...) {
+            return GLM_ERR_ALLOC;
+        }
+    }
+    const int nb = std::min((max_seq_len + g.block_size - 1) / g.block_size, max_blocks);
+    ProfileScope prof(kKernelGatherTokens, st);
+    hipLaunchKernelGGL(gather_tokens_kernel, dim3(nb, B), dim3(kCopyThreads), 0, st, (const u32x4 *)kv_pool_dev, block_tables_dev,
+                       seq_lens_dev, dst_offsets_dev, (u32x4 *)dst_dev, max_blocks, g.num_kv_heads, g.head_dim * 2 / 16,
+                       g.num_blocks);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? GLM_OK : set_hip_error(e);
 }

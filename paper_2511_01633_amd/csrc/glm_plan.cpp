@@ -240,7 +240,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     }
     if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb_family = cb_single = std::max(1, forced);
     const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 3);
-    int32_t cb_coop = (int32_t)std::max<int64_t>(32, units_coop * p.g.num_kv_heads / std::max(1, target_coop));
+    int32_t cb_coop = (int32_t)std::max<int64_t>(env_int("GLM_PLAN_COOP_MIN_CHUNK_BLOCKS", 16), units_coop * p.g.num_kv_heads / std::max(1, target_coop));
     cb_coop = (cb_coop + 1) & ~1;
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
     auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };

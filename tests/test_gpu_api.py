@@ -216,3 +216,24 @@ def test_kv_append_bit_exact_then_attention(hkv, d):
     ref = oracle.attention(w.geom, ref_pool, w.q, w.block_tables, w.seq_lens, w.scale, cu_q_lens=w.cu_q_lens)
     assert np.abs(got - ref).max() <= gu.TOL
     assert glm.glm_kv_append(w.geom, dw.pool, gu.dev(k_pad), gu.dev(v_pad), torch.from_numpy(slots_pad).cuda(), 0) == 0
+
+
+def test_kv_gather_tokens_bit_exact():
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(77, prefix_groups=[[0, 1, 2]], prefix_tokens=[48], suffix_tokens=[5, 40, 0, 130], num_q_heads=8,
+                        num_kv_heads=2, head_dim=128)
+    g = w.geom
+    offs, total = [], 0
+    for r in range(w.B):
+        offs.append(total); total += 2 * g.num_kv_heads * int(w.seq_lens[r]) * g.head_dim
+    ref = np.full(total + 64, 0x1234, np.uint16)
+    oracle.gather_tokens(g, w.pool, w.block_tables, w.seq_lens, offs, ref)
+    dst = torch.from_numpy(np.full(total + 64, 0x1234, np.uint16).view(np.int16)).cuda()
+    dw = gu.DeviceWorkload(w)
+    glm.glm_kv_gather_tokens(g, dw.pool, dw.tables, w.max_blocks, dw.seq_lens, torch.tensor(offs, dtype=torch.int64).cuda(),
+                             w.B, int(w.seq_lens.max()), dst)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.host_u16(dst), ref)
+    assert glm.glm_kv_gather_tokens(g, dw.pool, dw.tables, w.max_blocks, dw.seq_lens, torch.tensor(offs, dtype=torch.int64).cuda(),
+                                    0, 0, dst) == 0

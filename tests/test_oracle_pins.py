@@ -284,3 +284,31 @@ def test_new_token_slots_point_at_the_rows_attention_reads_last():
     sd = W.new_token_slots(wd)
     for r in range(2):
         L = int(wd.seq_lens[r]); assert sd[r] == wd.block_tables[r, (L - 1) // 4] * 4 + (L - 1) % 4
+
+
+def test_gather_tokens_matches_indexing_and_dense_attention():
+    """The dense copy is what numpy indexing through the table gives, and attention on it (one-request pool,
+    identity table) equals paged attention: the token gather is the inverse of paging."""
+    w = _small_decode(21, [5, 17, 0], prefix=8)
+    g = w.geom
+    bs, d, hkv = g.block_size, g.head_dim, g.num_kv_heads
+    offs, total = [], 0
+    for r in range(w.B):
+        offs.append(total); total += 2 * hkv * int(w.seq_lens[r]) * d
+    dst = np.full(total + 16, 0xABCD, np.uint16)
+    oracle.gather_tokens(g, w.pool, w.block_tables, w.seq_lens, offs, dst)
+    assert (dst[total:] == 0xABCD).all()
+    paged = oracle.attention(g, w.pool, w.q, w.block_tables, w.seq_lens, w.scale)
+    for r in range(w.B):
+        L = int(w.seq_lens[r])
+        dense = dst[offs[r]:offs[r] + 2 * hkv * L * d].reshape(2, hkv, L, d)
+        for j in range(L):
+            blk = int(w.block_tables[r, j // bs])
+            np.testing.assert_array_equal(dense[:, :, j, :], w.pool[blk, :, :, j % bs, :])
+        # dense attention with plain numpy
+        for h in range(g.num_q_heads):
+            kvh = h // (g.num_q_heads // hkv)
+            K = W.bf16_bits_to_f32(dense[0, kvh]).astype(np.float64); V = W.bf16_bits_to_f32(dense[1, kvh]).astype(np.float64)
+            s = float(w.scale) * K @ W.bf16_bits_to_f32(w.q[r, h]).astype(np.float64)
+            p = np.exp(s - s.max()); p /= p.sum()
+            assert np.abs(p @ V - paged[r, h]).max() < 1e-12

@@ -21,6 +21,7 @@ from .gen import (  # noqa: F401
     make_config,
     tiny_decode,
     llama8b_decode,
+    qwen3_moe_decode,
     prefill_on_prefix,
     tree_decode_70b,
     eviction_churn,

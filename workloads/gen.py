@@ -317,6 +317,21 @@ def llama8b_decode(seed: Optional[int] = None, *, branches: int = 64, prefixes: 
                          num_q_heads=32, num_kv_heads=8, head_dim=128, name="llama8b_decode")
 
 
+def qwen3_moe_decode(seed: Optional[int] = None, *, branches: int = 64, prefixes: int = 4,
+                     prefix_tokens: int = 2048, suffix_lo: int = 128, suffix_hi: int = 1024) -> Workload:
+    """The 8B decode batch at the per-layer attention shape of the model the paper served (Sec. 6.1,
+    Qwen3-235B-A22B; shape from its public configuration: 64 Q / 4 KV heads, d=128, i.e. 16 query rows per
+    branch and kv head): 2 KiB of K/V per token."""
+    seed = config_seed(5) if seed is None else seed
+    r2 = _rng(seed ^ 0x5EED)
+    sfx = r2.integers(suffix_lo, suffix_hi + 1, size=branches)
+    order = r2.permutation(branches)
+    per = branches // prefixes
+    groups = [sorted(int(x) for x in order[k * per:(k + 1) * per]) for k in range(prefixes)]
+    return custom_decode(seed, prefix_groups=groups, prefix_tokens=[prefix_tokens] * prefixes, suffix_tokens=sfx,
+                         num_q_heads=64, num_kv_heads=4, head_dim=128, name="qwen3_moe_decode")
+
+
 def prefill_on_prefix(seed: Optional[int] = None, *, branches: int = 16, prefix_tokens: int = 4096,
                       q_len: int = 512) -> Workload:
     """16 branches each appending 512 tokens onto one cached 4096-token prefix."""
