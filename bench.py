@@ -35,7 +35,7 @@ def _parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
-    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3 (default all)")
+    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3,mixed (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-headline", action="store_true",
                     help="profiling aid: run only the workloads named by --only and print their records")
@@ -229,6 +229,36 @@ def bench_churn(glm, W, w, steps, warmup, variants=4):
     return res
 
 
+def bench_mixed(glm, w, steps, warmup):
+    """Prefill branches and one-token (decode) branches in one call, with the mixed plan and, for comparison, with
+    every row treated as a prefill tile (GLM_PLAN_MIXED=0 at plan time)."""
+    import torch
+    g = w.geom
+    pool, q, tables, lens, cu = _dev(w.pool), _dev(w.q), _dev(w.block_tables), _dev(w.seq_lens), _dev(w.cu_q_lens)
+    out = torch.empty((w.sum_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    mq = int(w.q_lens.max())
+    res = {"workload": w.name, "requests": int(w.B), "one_token_requests": int((w.q_lens == 1).sum()), "flops": w.flops(),
+           "unique_kv_bytes": w.unique_kv_bytes()}
+    for name, flag in (("mixed_plan", "1"), ("all_rows_as_prefill_tiles", "0")):
+        old = os.environ.get("GLM_PLAN_MIXED")
+        os.environ["GLM_PLAN_MIXED"] = flag
+        try:
+            plan = glm.glm_plan_create(g, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+        finally:
+            if old is None:
+                os.environ.pop("GLM_PLAN_MIXED", None)
+            else:
+                os.environ["GLM_PLAN_MIXED"] = old
+        ws = torch.empty(max(16, plan.workspace_bytes), dtype=torch.uint8, device="cuda")
+
+        def step(i):
+            glm.glm_attn_prefill_on_prefix(g, pool, q, out, tables, w.max_blocks, lens, cu, w.B, w.sum_q, mq, w.scale, plan, ws)
+
+        ms = _time_steps(step, steps, warmup)
+        res[name] = {"ms_per_step": ms, "kernels": _kernel_times(glm, step, min(steps, 16)), "TFLOPs": w.flops() / ms / 1e9}
+    return res
+
+
 def bench_gather_tokens(glm, w, steps, warmup):
     """Every request of the batch made dense through its block table (shared prefixes are copied once per branch)."""
     import torch
@@ -341,7 +371,7 @@ def main():
         sys.exit(1)
     import paper_2511_01633_amd as glm
     import workloads as W
-    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3"}
+    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3", "mixed"}
     torch.cuda.set_device(0)
     extra = {}
 
@@ -353,6 +383,8 @@ def main():
                                                     max(2, args.warmup // 4))
         if "churn" in only:
             extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
+        if "mixed" in only:
+            extra["mixed_batch"] = bench_mixed(glm, W.mixed_batch(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "qwen3" in only:
             extra["qwen3_moe_decode"] = bench_decode(glm, W.qwen3_moe_decode(), args.layers, max(10, args.steps // 2),
                                                      max(2, args.warmup // 2))

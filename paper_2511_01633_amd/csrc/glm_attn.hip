@@ -44,6 +44,7 @@ struct AttnArgs {
     int32_t items_per_xcd;      // planned prefill: work items per XCD (list length / 8)
     int32_t q_rows;             // rows of Q / out (bounds the row index derived from cu_q_lens)
     float scale_log2;           // scale * log2(e)
+    const int32_t *q_row_of;    // wave-private launch of a mixed batch: request -> its row of Q / out (nullptr: r)
 };
 
 struct MergeArgs {
@@ -54,6 +55,8 @@ struct MergeArgs {
     const int32_t *merge_slots, *merge_kind, *merge_cnt;   // nullptr: implicit
     int32_t merge_stride;
     int32_t Hq, max_blocks, n_split, chunk_blocks;
+    const int32_t *q_row_of;    // mixed batch: request -> its row of out (nullptr: r)
+    int32_t q_rows;
 };
 
 __device__ __forceinline__ int wave_max(int v) {
@@ -657,7 +660,7 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
     int limit = 0;
     if (valid) {
         const int r = c.mem_off < 0 ? c.rep : a.members[c.mem_off + mi];
-        q_row = r;
+        q_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
         limit = a.seq_lens[r];
     }
     const int head = kvh * G + gh;
@@ -827,7 +830,8 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
     const int r = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
     const int lane = threadIdx.x;
     constexpr int E = D / 64;
-    float *dst = a.out + ((int64_t)r * a.Hq + h) * D + lane * E;
+    const int64_t out_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
+    float *dst = a.out + (out_row * a.Hq + h) * D + lane * E;
     int n, first = 0;
     const int32_t *slots = nullptr;
     if (a.merge_kind) {
@@ -1083,7 +1087,6 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
                                const int32_t *block_tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev,
                                const int32_t *cu_q_lens_dev, int32_t B, int32_t sum_q, int32_t max_q_len, float scale,
                                const glm_plan *plan, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace_dev; (void)workspace_bytes;
     if (int st = check_geom(g)) return st;
     if (B < 0 || max_blocks <= 0 || sum_q < 0 || max_q_len < 0 || !(scale > 0.f)) return GLM_ERR_GEOM;
     if (B == 0 || sum_q == 0) return GLM_OK;
@@ -1115,7 +1118,37 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         a.mode = kPlanned;
         a.chunks = plan->d.chunks[1];
         a.items_per_xcd = std::max(1, plan->d.n_chunks[1] / kXcds);
+        // a mixed batch: its one-token requests run as split-K items of the wave-private launch and are merged
+        const bool has_decode_rows = plan->d.n_chunks[0] > 0;
+        const size_t slot_bytes = (size_t)Hq * (size_t)(D + 2) * sizeof(float);
+        if (has_decode_rows && plan->n_slots > 0 &&
+            (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < (size_t)plan->n_slots * slot_bytes))
+            return GLM_ERR_WORKSPACE;
         e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+        if (e == hipSuccess && has_decode_rows) {
+            a.chunks = plan->d.chunks[0];
+            a.members = plan->d.members;
+            a.block_ids = plan->d.block_ids;
+            a.q_row_of = cu_q_lens_dev;
+            a.part_ml = (float *)workspace_dev;
+            a.part_acc = a.part_ml + (size_t)plan->n_slots * (size_t)Hq * 2;
+            e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
+            if (e == hipSuccess) {
+                MergeArgs m{};
+                m.out = (float *)out_dev;
+                m.seq_lens = seq_lens_dev;
+                m.Hq = Hq; m.max_blocks = max_blocks;
+                m.part_ml = a.part_ml;
+                m.part_acc = a.part_acc;
+                m.merge_slots = plan->d.merge_slots;
+                m.merge_kind = plan->d.merge_kind;
+                m.merge_cnt = plan->d.merge_cnt;
+                m.merge_stride = plan->merge_stride;
+                m.q_row_of = cu_q_lens_dev;
+                m.q_rows = sum_q;
+                e = launch_merge(D, m, B * Hq, st);
+            }
+        }
     } else {
         if (max_q_len == 0) return GLM_OK;
         a.mode = kImplicitPrefill;

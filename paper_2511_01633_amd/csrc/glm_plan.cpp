@@ -186,22 +186,31 @@ std::vector<Work> pack_quads(std::vector<Item> &families, std::vector<Item> &sin
     return out;
 }
 
-int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
+// subset == nullptr: every request decodes.  Otherwise only the listed requests (the one-token rows of a mixed
+// batch) are planned here, everything goes to the wave-private launch, and the cooperative list is left alone.
+int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, const std::vector<int32_t> *subset = nullptr) {
     const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
     std::vector<int32_t> nblk(B);
     for (int32_t r = 0; r < B; ++r) {
         if (seq_lens[r] < 0 || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks) return GLM_ERR_RANGE;
         nblk[r] = ceil_div(seq_lens[r], kBlockSize);
     }
-    std::vector<int32_t> all(B);
-    std::iota(all.begin(), all.end(), 0);
+    std::vector<int32_t> all;
+    if (subset) {
+        all = *subset;
+    } else {
+        all.resize(B);
+        std::iota(all.begin(), all.end(), 0);
+    }
+    std::vector<char> planned(B, 0);
+    for (int32_t r : all) planned[r] = 1;
     std::vector<Segment> segs;
-    if (B > 0) build_segments(tables, p.max_blocks, nblk, all, 0, segs);
+    if (!all.empty()) build_segments(tables, p.max_blocks, nblk, all, 0, segs);
 
     // Segments with many rows go to the cooperative kernel (64 rows per workgroup share one staged
     // K/V tile); the rest is cut into wave-private items of 16 rows.
     const int coop_min_rows = env_int("GLM_PLAN_COOP_MIN_ROWS", 128);
-    auto is_coop = [&](int64_t rows) { return rows >= coop_min_rows; };
+    auto is_coop = [&](int64_t rows) { return !subset && rows >= coop_min_rows; };
     // Chunk length, separately for the two launches.  Wave-private items: a little fewer items than the
     // chip has wave slots (2 per SIMD = 2048), so that the launch, padding included, is one round; at
     // least 4 tiles each.
@@ -331,24 +340,31 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens) {
     for (int32_t r = 0; r < B; ++r) {
         p.merge_off[r] = (int32_t)(r * stride);
         p.merge_cnt[r] = (int32_t)per_req[r].size();
-        if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
+        if (!planned[r]) p.merge_kind[r] = kMergeDirect;          // somebody else writes (or there is nothing to write)
+        else if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
         else if (per_req[r].empty()) p.merge_kind[r] = kMergeDirect;
         std::copy(per_req[r].begin(), per_req[r].end(), p.merge_slots.begin() + (size_t)r * stride);
     }
     p.merge_off[B] = (int32_t)((size_t)B * stride);
     std::vector<Work> quads = pack_quads(families, singles);
     p.chunks[0] = deal_to_xcds(quads, 4);
-    p.chunks[1] = deal_to_xcds(coop, 1);
+    if (!subset) p.chunks[1] = deal_to_xcds(coop, 1);
     return GLM_OK;
 }
 
-int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
+// Mixed batches: a request with one new token is a decode step (Sec. 2.4) in the middle of other requests'
+// prefills; those rows are planned like a decode batch of their own (prefix tree over them, split-K items for
+// the wave-private launch, merge lists), the others as 128-row tiles of the cooperative launch.
+int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, const int32_t *q_lens) {
     const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
     const int32_t tile_rows = kCoopRows;
+    const bool mixed = env_int("GLM_PLAN_MIXED", 1) != 0 && G <= kRowsPerWave;
+    std::vector<int32_t> one_token;
     std::vector<Work> work;
     for (int32_t r = 0; r < B; ++r) {
         if (q_lens[r] < 0 || seq_lens[r] < q_lens[r] || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks)
             return GLM_ERR_RANGE;
+        if (mixed && q_lens[r] == 1) { one_token.push_back(r); continue; }
         const int64_t rows = (int64_t)q_lens[r] * G;
         const int64_t ctx = seq_lens[r] - q_lens[r];
         for (int64_t row0 = 0; row0 < rows; row0 += tile_rows) {
@@ -381,6 +397,7 @@ int build_prefill(glm_plan &p, const int32_t *seq_lens, const int32_t *q_lens) {
     p.merge_stride = 1;
     p.merge_kind.assign(B, kMergeDirect);
     p.n_slots = 0;
+    if (!one_token.empty()) return build_decode(p, tables, seq_lens, &one_token);
     return GLM_OK;
 }
 
@@ -419,7 +436,7 @@ static glm_plan *plan_build(glm_geom g, const int32_t *tables, int32_t max_block
             p->B = B;
             p->max_blocks = max_blocks;
             p->kind = q_lens ? kPrefill : kDecode;
-            st = q_lens ? build_prefill(*p, seq_lens, q_lens) : build_decode(*p, tables, seq_lens);
+            st = q_lens ? build_prefill(*p, tables, seq_lens, q_lens) : build_decode(*p, tables, seq_lens);
         } catch (const std::bad_alloc &) {
             st = GLM_ERR_ALLOC;
         } catch (...) {

@@ -46,8 +46,11 @@ class DeviceWorkload:
     def prefill(self, plan=None):
         w = self.w
         self.out.fill_(float("nan"))
+        ws = None
+        if plan is not None and plan.workspace_bytes > 0:
+            ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
         glm.glm_attn_prefill_on_prefix(w.geom, self.pool, self.q, self.out, self.tables, w.max_blocks, self.seq_lens,
-                                       self.cu, w.B, w.sum_q, int(w.q_lens.max()) if w.B else 0, w.scale, plan, None)
+                                       self.cu, w.B, w.sum_q, int(w.q_lens.max()) if w.B else 0, w.scale, plan, ws)
         torch.cuda.synchronize()
         return self.out.cpu().numpy().astype(np.float64)
 

@@ -22,6 +22,7 @@ from .gen import (  # noqa: F401
     tiny_decode,
     llama8b_decode,
     qwen3_moe_decode,
+    mixed_batch,
     prefill_on_prefix,
     tree_decode_70b,
     eviction_churn,

@@ -255,9 +255,11 @@ def custom_decode(seed: int, *, prefix_groups: Sequence[Sequence[int]], prefix_t
 def custom_prefill(seed: int, *, prefix_groups: Sequence[Sequence[int]], prefix_tokens: Sequence[int],
                    q_lens: Sequence[int], num_q_heads: int, num_kv_heads: int, head_dim: int,
                    block_size: int = 16, occupancy: float = 0.9, permute: bool = True,
+                   cached_suffix_tokens: Optional[Sequence[int]] = None,
                    name: str = "custom_prefill") -> Workload:
     """Prefill batch: branch r appends q_lens[r] new tokens (already written to the
-    pool) after its group's cached prefix; seq_len = prefix + q_len."""
+    pool) after its group's cached prefix and, if given, cached_suffix_tokens[r] cached
+    tokens of its own; seq_len = prefix + cached suffix + q_len."""
     rng = _rng(seed)
     bs = block_size
     B = len(q_lens)
@@ -270,7 +272,7 @@ def custom_prefill(seed: int, *, prefix_groups: Sequence[Sequence[int]], prefix_
     seq = np.zeros(B, np.int32)
     for r in range(B):
         p = int(prefix_tokens[group_of[r]]) if group_of[r] >= 0 else 0
-        seq[r] = p + int(ql[r])
+        seq[r] = p + int(ql[r]) + (int(cached_suffix_tokens[r]) if cached_suffix_tokens is not None else 0)
     live = sum(shared_nb)
     for r in range(B):
         sn = shared_nb[group_of[r]] if group_of[r] >= 0 else 0
@@ -330,6 +332,23 @@ def qwen3_moe_decode(seed: Optional[int] = None, *, branches: int = 64, prefixes
     groups = [sorted(int(x) for x in order[k * per:(k + 1) * per]) for k in range(prefixes)]
     return custom_decode(seed, prefix_groups=groups, prefix_tokens=[prefix_tokens] * prefixes, suffix_tokens=sfx,
                          num_q_heads=64, num_kv_heads=4, head_dim=128, name="qwen3_moe_decode")
+
+
+def mixed_batch(seed: Optional[int] = None, *, prefill_branches: int = 8, decode_branches: int = 64,
+                prefix_tokens: int = 2048, q_len: int = 512, suffix_lo: int = 128, suffix_hi: int = 1024) -> Workload:
+    """Reasoning-agent prefills and action-agent decodes in one batch (the paper serves concurrent queries
+    whose agents are in different phases, Sec. 6.1): on one shared cached prefix, `prefill_branches` branches
+    append q_len new tokens each and `decode_branches` branches, each with a cached private suffix of
+    U{suffix_lo..suffix_hi} tokens, append one.  Llama-3-8B attention shape."""
+    seed = config_seed(6) if seed is None else seed
+    r2 = _rng(seed ^ 0x5EED)
+    B = prefill_branches + decode_branches
+    kind = np.zeros(B, bool)
+    kind[r2.permutation(B)[:prefill_branches]] = True                # which branches prefill
+    q_lens = [q_len if kind[r] else 1 for r in range(B)]
+    sfx = [0 if kind[r] else int(r2.integers(suffix_lo, suffix_hi + 1)) for r in range(B)]
+    return custom_prefill(seed, prefix_groups=[list(range(B))], prefix_tokens=[prefix_tokens], q_lens=q_lens,
+                          cached_suffix_tokens=sfx, num_q_heads=32, num_kv_heads=8, head_dim=128, name="mixed_batch")
 
 
 def prefill_on_prefix(seed: Optional[int] = None, *, branches: int = 16, prefix_tokens: int = 4096,
