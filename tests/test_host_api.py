@@ -149,3 +149,10 @@ def test_prefill_plan_tiles_every_row():
     assert all(v == 1 for v in rows.values())
     assert len(rows) == int(q_lens.sum()) * 4
     assert plan.workspace_bytes <= 256
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
