@@ -207,14 +207,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     for (int s = 0; s < KSTEPS; ++s) {
         if (valid) {
             qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + (q_row * a.Hq + head) * D + 16 * s + 8 * h2);
-            // Long runs: the factor scale*log2(e) goes into Q (rounded to bf16 again), and the softmax
-            // reference into the accumulator the QK^T chain starts from, so that the MFMAs deliver the
-            // exponent itself.  The extra rounding of Q moves a single weight by ~1e-3 relative, which
-            // averages out over > kSplitLimit keys; short runs keep the exact path.
-            if (!split) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)((float)qreg[s][j] * a.scale_log2);
-            }
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) qreg[s][j] = (__bf16)0.0f;
@@ -228,9 +220,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
     float m_run = -INFINITY;
     float l_run = 0.f;      // this lane's share of the row sum (its 16 of every 32 tokens)
-    f32x16 c_init;          // what a QK^T chain starts from: 0, or minus the reference on long runs
-#pragma unroll
-    for (int i = 0; i < 16; ++i) c_init[i] = 0.f;
 
     const int32_t *table = a.tables + (int64_t)c.rep * a.max_blocks;
     const int64_t blk_bytes = 2 * (int64_t)a.Hkv * kBlockSize * ROWB;
@@ -317,7 +306,9 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     // S^T = K . Q^T of the tile in ring stage `stage`: one accumulator, KSTEPS dependent MFMAs
     auto qk = [&](int stage) -> f32x16 {
         const int kb = k_rd + stage * STAGE_B;
-        f32x16 sT = c_init;
+        f32x16 sT;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sT[i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ring + (kb ^ (ks << 5)));
@@ -344,8 +335,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int i = 8 * s2 + j;
-                const float pf = SPLIT ? __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use))
-                                       : __builtin_amdgcn_exp2f(sT[i]);
+                const float pf = __builtin_amdgcn_exp2f(__builtin_fmaf(sT[i], a.scale_log2, -m_use));
                 const __bf16 h = (__bf16)pf;
                 hi[s2][j] = h;
                 if (SPLIT) {
@@ -402,7 +392,8 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         }
         f32x16 s_next = sT;
         if (FAST || t + 1 < ntiles) {
-            s_next = c_init;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qreg[ks], s_next, 0, 0, 0);
         }
@@ -413,7 +404,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         // are rescaled and this tile's weights taken again.  Weights thus stay <= 2^kLazyLog2 and the
         // quotient acc / l is unchanged; the common path has no maximum, no exchange between the two lanes
         // of a row and no branch between the QK^T MFMAs and the exponentials.
-        const float m_use = (SPLIT && m_run != -INFINITY) ? m_run : 0.f;
+        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
         bf16x8 p_hi[2], p_lo[2];
         float psum = weights(split_tag, m_use, p_hi, p_lo);
         // V^T fragments of tile t, requested before the check below so that they have landed when PV starts
@@ -433,26 +424,10 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
 #pragma unroll
             for (int i = 1; i < 16; ++i) m_tile = fmaxf(m_tile, sT[i]);
             m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
-            float m_new, alpha, m_new_use;
-            if (SPLIT) {
-                // sT holds raw scores; scale*log2(e) (> 0) is folded into the exponent
-                m_new = fmaxf(m_run, m_tile * a.scale_log2);
-                m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
-                alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
-            } else {
-                // sT holds exponents relative to the reference (c_init = -reference went into the MFMA chain)
-                const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
-                m_new = fmaxf(m_run, m_old + m_tile);
-                m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
-                alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
-                const float delta = m_new_use - m_old;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { sT[i] -= delta; c_init[i] = -m_new_use; }
-                if (FAST || t + 1 < ntiles) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s_next[i] -= delta;
-                }
-            }
+            // sT holds raw scores; scale*log2(e) (> 0) is folded into the exponent
+            const float m_new = fmaxf(m_run, m_tile * a.scale_log2);
+            const float m_new_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);
             l_run *= alpha;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
@@ -460,7 +435,7 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
                 for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
             m_run = m_new;
             sum_thr = (m_new == -INFINITY) ? -1.0f : kLazySum;
-            psum = weights(split_tag, SPLIT ? m_new_use : 0.f, p_hi, p_lo);
+            psum = weights(split_tag, m_new_use, p_hi, p_lo);
         }
         l_run += psum;
 #pragma unroll

@@ -371,3 +371,33 @@ def test_mixed_batch_needs_its_workspace():
     st = glm.glm_attn_prefill_on_prefix(w.geom, dw.pool, dw.q, dw.out, dw.tables, w.max_blocks, dw.seq_lens, dw.cu, w.B, w.sum_q,
                                         int(w.q_lens.max()), w.scale, plan, None, check=False)
     assert glm.glm_status_string(st) == "workspace missing or too small"
+
+
+def test_mixed_batch_full_sampled():
+    """The bench's mixed batch at full size: every one-token request plus sampled prefill rows against the oracle."""
+    gu = _gu()
+    w = W.mixed_batch()
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    got = dw.prefill(plan)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(15)
+    one = np.flatnonzero(w.q_lens == 1)
+    many = np.flatnonzero(w.q_lens > 1)
+    req = np.concatenate([one, rng.choice(many, 64)]).astype(np.int32)
+    idx = np.array([0 if w.q_lens[r] == 1 else rng.integers(0, int(w.q_lens[r])) for r in req], np.int32)
+    head = rng.integers(0, w.geom.num_q_heads, size=req.size).astype(np.int32)
+    ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head, sel_i=idx,
+                                cu_q_lens=w.cu_q_lens)
+    _check(got[w.cu_q_lens[req] + idx, head], ref, "mixed_batch (%d sampled rows)" % req.size)
+
+
+def test_qwen3_shape_decode_full_sampled():
+    gu = _gu()
+    w = W.qwen3_moe_decode()
+    dw = gu.DeviceWorkload(w)
+    got = dw.decode(plan=dw.make_plan())
+    assert np.isfinite(got).all()
+    req, _, head = _sample_rows(w, 256, 16)
+    ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head)
+    _check(got[req, head], ref, "qwen3_moe_decode (256 sampled rows)")
