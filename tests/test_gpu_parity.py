@@ -401,3 +401,26 @@ def test_qwen3_shape_decode_full_sampled():
     req, _, head = _sample_rows(w, 256, 16)
     ref = oracle.attention_rows(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, req, head)
     _check(got[req, head], ref, "qwen3_moe_decode (256 sampled rows)")
+
+
+@pytest.mark.parametrize("peaks", [1, 2, 8])
+def test_long_run_with_dominant_keys(peaks):
+    """A run long enough for the plain-bf16 weight path (> 1024 keys) in which a few keys with large scores carry
+    almost all of every row's weight: rounding anywhere in the exponent, or of the weights, shows here first."""
+    gu = _gu()
+    w = W.custom_prefill(4242, prefix_groups=[[0, 1]], prefix_tokens=[2048], q_lens=[160, 130], num_q_heads=8, num_kv_heads=2,
+                         head_dim=128)
+    g = w.geom
+    q = W.bf16_bits_to_f32(w.q)
+    pool = w.pool.copy()
+    rng = np.random.default_rng(peaks)
+    for kvh in range(g.num_kv_heads):
+        qdir = q[:, kvh * 4:(kvh + 1) * 4, :].mean(axis=(0, 1))
+        qdir /= np.linalg.norm(qdir)
+        for j in rng.choice(2048, peaks, replace=False):
+            blk, t = int(w.block_tables[0, j // 16]), j % 16
+            pool[blk, 0, kvh, t, :] = W.f32_to_bf16_bits(rng.standard_normal(128).astype(np.float32) + 40.0 * qdir)
+    w2 = W.Workload("peaked", g, pool, w.q, w.block_tables, w.seq_lens, w.scale, q_lens=w.q_lens, cu_q_lens=w.cu_q_lens)
+    ref = _oracle(w2)
+    dw = gu.DeviceWorkload(w2)
+    _check(dw.prefill(dw.make_plan()), ref, "long run, %d dominant keys" % peaks)
