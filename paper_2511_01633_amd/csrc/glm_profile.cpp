@@ -1,5 +1,6 @@
 // Optional per-kernel timing with HIP events recorded on the stream each kernel is launched on.
 // Off by default: the hot calls then record nothing.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -10,15 +11,12 @@ namespace glm {
 namespace {
 struct Sample { hipEvent_t start, stop; int id; };
 std::mutex g_mu;
-bool g_enabled = false;
+std::atomic<bool> g_enabled{false};       // read by every launch: no lock on the hot path
 std::vector<Sample> g_samples;
 }  // namespace
 
 ProfileScope::ProfileScope(int id, hipStream_t st) : st_(st), id_(id) {
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        active_ = g_enabled;
-    }
+    active_ = g_enabled.load(std::memory_order_relaxed);
     if (!active_) return;
     if (hipEventCreate(&start_) != hipSuccess || hipEventCreate(&stop_) != hipSuccess ||
         hipEventRecord(start_, st_) != hipSuccess)
@@ -39,8 +37,7 @@ using namespace glm;
 extern "C" {
 
 int glm_profile_enable(int on) {
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_enabled = on != 0;
+    g_enabled.store(on != 0, std::memory_order_relaxed);
     return GLM_OK;
 }
 
