@@ -237,3 +237,33 @@ def test_kv_gather_tokens_bit_exact():
     np.testing.assert_array_equal(gu.host_u16(dst), ref)
     assert glm.glm_kv_gather_tokens(g, dw.pool, dw.tables, w.max_blocks, dw.seq_lens, torch.tensor(offs, dtype=torch.int64).cuda(),
                                     0, 0, dst) == 0
+
+
+def test_hot_calls_can_be_captured_in_a_graph():
+    """The hot calls allocate nothing and record no memset: a captured decode step (streaming launch + merge) replays
+    to the eager result, with eager work of the program between the replays."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(9100, prefix_groups=[[0, 1, 2, 3]], prefix_tokens=[256], suffix_tokens=[40, 300, 7, 129, 700],
+                        num_q_heads=8, num_kv_heads=2, head_dim=128)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    eager = dw.decode(plan=plan, workspace=ws)
+    out = torch.zeros_like(dw.out)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        glm.glm_attn_decode(w.geom, dw.pool, dw.q, out, dw.tables, w.max_blocks, dw.seq_lens, w.B, w.scale, plan, ws)   # warm-up
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            glm.glm_attn_decode(w.geom, dw.pool, dw.q, out, dw.tables, w.max_blocks, dw.seq_lens, w.B, w.scale, plan, ws)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        scratch = torch.randn(1 << 16, device="cuda").sum()          # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy().astype(np.float64), eager)
+        assert bool(torch.isfinite(scratch))
