@@ -352,7 +352,7 @@ def cpu_baseline(w, unit_bytes):
         oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale, nthreads=cores)
         reps += 1
         el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 50:
+        if el > 10.0 or reps >= 400:
             break
     return {"value": unit_bytes * reps / el / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": "%d full passes of the fp64 oracle over the whole %s batch (%d branches x %d q heads, no prefix "
