@@ -326,6 +326,12 @@ def reference_rates(glm):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     mfma_tflops = wgs * 4 * iters * 4 * 32768 / dt / 1e12
+    glm.glm_bench_mfma_varied(sink, wgs, 100)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    glm.glm_bench_mfma_varied(sink, wgs, iters)
+    torch.cuda.synchronize()
+    varied_tflops = wgs * 4 * iters * 4 * 32768 / (time.perf_counter() - t0) / 1e12
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty(n, dtype=torch.uint8, device="cuda")
@@ -338,7 +344,8 @@ def reference_rates(glm):
         glm.glm_bench_copy(src, dst, n)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
-    return {"mfma_bf16_32x32x16_TFLOPs_measured": mfma_tflops, "copy_1GiB_GBps_read_plus_write": 2 * n / dt / 1e9}
+    return {"mfma_bf16_32x32x16_TFLOPs_measured": mfma_tflops, "mfma_bf16_32x32x16_TFLOPs_varied_operands": varied_tflops,
+            "copy_1GiB_GBps_read_plus_write": 2 * n / dt / 1e9}
 
 
 def cpu_baseline(w, unit_bytes):

@@ -232,10 +232,15 @@ GLM_API int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches)
  * glm_bench_mfma: `workgroups` workgroups of 4 waves each issue iters*4 v_mfma_f32_32x32x16_bf16
  *   (32768 flop per instruction per wave) and nothing else; timing it gives the bf16 matrix rate the
  *   chip sustains at the clock it actually holds.  sink_dev: at least 4 bytes of device memory.
+ * glm_bench_mfma_varied: the same instruction stream, but the operands' signs, exponents and mantissas
+ *   differ from lane to lane and chain to chain (glm_bench_mfma multiplies constants).  The clock the
+ *   chip holds under the matrix units depends on how many operand bits toggle, so this is the rate real
+ *   data can reach; a kernel's matrix-pipe utilisation is fairly judged against it.
  * glm_bench_copy: dst[i] = src[i] over `bytes` bytes (multiple of 16, both pointers 16-byte aligned),
  *   a plain streaming copy of known size: the calibration point for HBM traffic counters.
  */
 GLM_API int glm_bench_mfma(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_stream);
+GLM_API int glm_bench_mfma_varied(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_stream);
 GLM_API int glm_bench_copy(const void *src_dev, void *dst_dev, size_t bytes, void *hip_stream);
 
 #ifdef __cplusplus

@@ -29,6 +29,44 @@ __global__ void __launch_bounds__(256) mfma_peak_kernel(float *sink, int iters) 
     if (r == -1.f) sink[0] = r;   // never true; keeps the loop alive
 }
 
+// The same instruction stream on operands whose bits differ from lane to lane and from chain to chain
+// (signs, three exponents and all mantissa bits drawn from a hash of the lane's index).  The clock the
+// chip holds depends on how many bits toggle, so this is the matrix rate that real data can reach.
+__device__ __forceinline__ unsigned mix32(unsigned x) {
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+__global__ void __launch_bounds__(256) mfma_varied_kernel(float *sink, int iters) {
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        s16x8 ta, tb;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const unsigned h = mix32((blockIdx.x * 256u + threadIdx.x) * 64u + r * 16u + j);
+            // |x| in [0.25, 4): products and sums stay far from overflow for any iteration count that finishes
+            ta[j] = (short)(((h & 1u) << 15) | ((0x7du + ((h >> 1) & 3u)) << 7) | ((h >> 3) & 0x7fu));
+            tb[j] = (short)((((h >> 10) & 1u) << 15) | ((0x7du + ((h >> 11) & 3u)) << 7) | ((h >> 13) & 0x7fu));
+        }
+        a[r] = __builtin_bit_cast(bf16x8, ta);
+        b[r] = __builtin_bit_cast(bf16x8, tb);
+    }
+    f32x16 c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 0.f; c2[i] = 0.f; c3[i] = 0.f; }
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += c0[i] + c1[i] + c2[i] + c3[i];
+    if (r == -1.2345f) sink[0] = r;   // never true (the sums are multiples of 2^-18 of far larger size); keeps the loop alive
+}
+
 // dst[i] = src[i] for n 16-byte pieces, 4 pieces in flight per thread
 __global__ void __launch_bounds__(256) plain_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
     const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
@@ -49,6 +87,14 @@ int glm_bench_mfma(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_
     if (!sink_dev) return GLM_ERR_NULL;
     if (workgroups <= 0 || iters <= 0) return GLM_ERR_GEOM;
     hipLaunchKernelGGL(mfma_peak_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink_dev, iters);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GLM_OK : set_hip_error(e);
+}
+
+int glm_bench_mfma_varied(void *sink_dev, int32_t workgroups, int32_t iters, void *hip_stream) {
+    if (!sink_dev) return GLM_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0) return GLM_ERR_GEOM;
+    hipLaunchKernelGGL(mfma_varied_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink_dev, iters);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? GLM_OK : set_hip_error(e);
 }

@@ -131,6 +131,7 @@ def test_reference_kernels():
     glm.glm_bench_copy(src, dst, src.numel() * 4)
     sink = torch.zeros(16, dtype=torch.float32, device="cuda")
     glm.glm_bench_mfma(sink, 64, 10)
+    glm.glm_bench_mfma_varied(sink, 64, 10)
     torch.cuda.synchronize()
     assert torch.equal(src, dst) and float(sink.abs().sum()) == 0.0
     glm.glm_profile_reset()
