@@ -127,7 +127,8 @@ def bench_decode(glm, w, layers, steps, warmup):
     io_bytes = w.q.nbytes + out.numel() * 4
     tok = _kv_tokens_by_kind(plan, w)
     per_tok = 4 * g.num_kv_heads * g.head_dim
-    kern_bytes = {"attn_stream_w1": tok[1] * per_tok, "attn_stream_w4": tok[4] * per_tok}
+    kern_bytes = {"attn_stream_w1": tok[1] * per_tok, "attn_stream_w4": tok[4] * per_tok,
+                  "attn_stream_fused": (tok[1] + tok[4]) * per_tok}
     res = {
         "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "layers_rotated": len(pools),
         "unique_kv_bytes": kv_bytes, "logical_kv_bytes": w.logical_kv_bytes(), "flops": w.flops(),

@@ -32,7 +32,7 @@ EXPORTS = (
     "glm_cache_lookup", "glm_cache_block_tier", "glm_cache_drain_evicted", "glm_cache_stats",
 )
 GLM_ERR_CACHE_FULL = -9
-KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5, "kv_gather_tokens": 6}
+KERNEL_IDS = {"attn_stream_w1": 0, "attn_stream_w4": 1, "attn_merge": 2, "kv_gather": 3, "kv_fork_copy": 4, "kv_append": 5, "kv_gather_tokens": 6, "attn_stream_fused": 7}
 
 
 class glm_geom(ctypes.Structure):

@@ -44,7 +44,9 @@ struct AttnArgs {
     int32_t items_per_xcd;      // planned prefill: work items per XCD (list length / 8)
     int32_t q_rows;             // rows of Q / out (bounds the row index derived from cu_q_lens)
     float scale_log2;           // scale * log2(e)
-    const int32_t *q_row_of;    // wave-private launch of a mixed batch: request -> its row of Q / out (nullptr: r)
+    const int32_t *q_row_of;    // wave-private work of a mixed batch: request -> its row of Q / out (nullptr: r)
+    const glm_chunk *chunks_priv;   // fused launch: the wave-private list (chunks is the cooperative one)
+    int32_t fused_coop_per_xcd, fused_priv_per_xcd;   // fused launch: workgroups of each kind per XCD
 };
 
 struct MergeArgs {
@@ -98,8 +100,18 @@ __device__ __forceinline__ void wait_vmcnt() {       // s_waitcnt vmcnt(N) only 
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
+// Shared memory of a streaming workgroup: the cooperative body's ring + two small arrays, or the wave-private
+// body's four V tiles, whichever is larger (the fused launch runs either body in a workgroup).
 template <int D>
-__global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
+constexpr int stream_smem_bytes() {
+    constexpr int coop = 4 * 2 * 32 * 2 * D + 32;            // NS stages of a K and a V tile of 32 rows + wave_lim/min
+    constexpr int priv = 4 * 32 * (D + 16) * 2;              // one padded 32-row V tile per wave
+    return coop > priv ? coop : priv;
+}
+
+// The cooperative workgroup `L` of the list `chunks` (a.chunks is not used).
+template <int D>
+__device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chunk *chunks, const int L, unsigned char *smem) {
     constexpr int T = 32;                      // tokens per tile
     constexpr int ROWB = 2 * D;                // bytes of a K or V row
     constexpr int CH = ROWB / 16;              // 16-byte chunks per row
@@ -113,8 +125,10 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     constexpr int DT = D / 32;                 // 32-wide d tiles of O^T
     static_assert(IPW >= 1 && 16 % RPI == 0, "a wave instruction must stay inside one block");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE_B];
-    __shared__ int wave_lim[4], wave_min[4];
+    static_assert(NS * STAGE_B + 32 <= stream_smem_bytes<D>(), "shared memory layout");
+    unsigned char *const ring = smem;                                   // NS * STAGE_B bytes, 1024-aligned
+    int *const wave_lim = reinterpret_cast<int *>(smem + NS * STAGE_B);
+    int *const wave_min = wave_lim + 4;
 
     const int tid = threadIdx.x;
     __builtin_assume(tid >= 0 && tid < 256);
@@ -132,12 +146,11 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
         // list.  Decode: kv head fastest (row tiles of one chunk are neighbours in the list and meet in
         // L2).  Prefill: kv head slowest, so that the workgroups in flight on an XCD are the row tiles of
         // few (request, kv head) streams and each stream's K/V is pulled into that L2 once.
-        const int L = blockIdx.x;
         const int x = L % kXcds, k = L / kXcds;
         int ci;
         if (a.cu_q_lens) { kvh = k / a.items_per_xcd; ci = k % a.items_per_xcd; }
         else { kvh = k % a.Hkv; ci = k / a.Hkv; }
-        const glm_chunk *cp = a.chunks + (ci * kXcds + x);
+        const glm_chunk *cp = chunks + (ci * kXcds + x);
         c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
         c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
         c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
@@ -149,7 +162,6 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
     } else {
         // prefill without a plan: XCD x takes the requests x, x+8, ..; on it kv head is the slowest
         // index, then the request, then the row tile (same reason as above)
-        const int L = blockIdx.x;
         const int x = L % kXcds;
         int k = L / kXcds;
         const int t = k % a.row_tiles; k /= a.row_tiles;
@@ -536,29 +548,29 @@ __global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
 // current tile have consumed the staging registers, so they fly during the softmax and the
 // PV MFMAs of this wave and during everything the other waves of the SIMD do.
 // The arithmetic is the same as in the cooperative kernel above.
+// The wave-private workgroup `L` (four work items) of the list `chunks` (a.chunks is not used).
 template <int D>
-__global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_chunk *chunks, const int L, unsigned char *smem) {
     constexpr int VSTR = D + 16;
     constexpr int KS = D / 32;
     constexpr int DT = D / 16;
     constexpr int VPL = 16 * D / 8 / 64;   // 16-byte V pieces per lane per block
 
-    __shared__ __attribute__((aligned(16))) __bf16 v_lds_all[4][32 * VSTR];
+    static_assert(4 * 32 * VSTR * 2 <= stream_smem_bytes<D>(), "shared memory layout");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n16 = lane & 15;
     const int g4 = lane >> 4;
-    __bf16 *v_lds = v_lds_all[wave];
+    __bf16 *v_lds = reinterpret_cast<__bf16 *>(smem) + wave * (32 * VSTR);
 
     glm_chunk c;
     int kvh;
     const int G = a.G;
     if (a.mode == kPlanned) {
-        const int L = blockIdx.x;
         const int x = L % kXcds, k = L / kXcds;
         kvh = k % a.Hkv;
-        const glm_chunk *cp = a.chunks + (((k / a.Hkv) * kXcds + x) * 4 + wave);
+        const glm_chunk *cp = chunks + (((k / a.Hkv) * kXcds + x) * 4 + wave);
         c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
         c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
         c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
@@ -570,7 +582,7 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
         c.n_ids = __builtin_amdgcn_readfirstlane(cp->n_ids);
         if (c.n_mem == 0) return;
     } else {
-        int64_t I = (int64_t)blockIdx.x * 4 + wave;
+        int64_t I = (int64_t)L * 4 + wave;
         kvh = (int)(I % a.Hkv); I /= a.Hkv;
         const int rt = (int)(I % a.row_tiles); I /= a.row_tiles;
         const int s = (int)(I % a.n_split);
@@ -798,6 +810,35 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
     }
 }
 
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_coop_kernel(const AttnArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[stream_smem_bytes<D>()];
+    attn_coop_body<D>(a, a.chunks, (int)blockIdx.x, smem);
+}
+
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[stream_smem_bytes<D>()];
+    attn_private_body<D>(a, a.chunks, (int)blockIdx.x, smem);
+}
+
+// Both kinds of workgroups of a planned call in one launch.  The cooperative workgroups are bound by the
+// matrix units, the wave-private ones by HBM; launched one after the other each leaves the other's
+// resource idle, and the first launch's last, partly filled round of workgroups leaves CUs idle as well.
+// Here the k-th workgroup of an XCD is cooperative or wave-private such that both lists are used up at the
+// same rate.  Workgroup L still runs on XCD L % 8 and takes its XCD's next entry of its kind, so the
+// per-XCD balance and order of either list are kept.
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_fused_kernel(const AttnArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[stream_smem_bytes<D>()];
+    const int L = blockIdx.x;
+    const int x = L % kXcds, k = L / kXcds;
+    const int64_t nc = a.fused_coop_per_xcd, tot = nc + a.fused_priv_per_xcd;
+    const int before = (int)(k * nc / tot);                 // cooperative workgroups among this XCD's first k
+    if ((int)((k + 1) * nc / tot) > before) attn_coop_body<D>(a, a.chunks, before * kXcds + x, smem);
+    else attn_private_body<D>(a, a.chunks_priv, (k - before) * kXcds + x, smem);
+}
+
 // Combines a request's partial results in list order:
 //   M = max m_i,  l = sum l_i 2^(m_i-M),  out = sum acc_i 2^(m_i-M) / l.
 template <int D>
@@ -922,6 +963,26 @@ hipError_t launch_private(int D, const AttnArgs &args, int64_t grid, hipStream_t
     return hipGetLastError();
 }
 
+// GLM_FUSED=0 keeps the two streaming launches of a planned call apart (for comparison)
+bool fused_enabled() {
+    const char *s = std::getenv("GLM_FUSED");
+    return !(s && s[0] == '0');
+}
+
+// a: cooperative list in a.chunks (n_coop entries), wave-private list in a.chunks_priv (n_priv entries)
+hipError_t launch_fused(int D, AttnArgs &a, int64_t n_coop, int64_t n_priv, hipStream_t st) {
+    const int64_t coop_per_xcd = n_coop / kXcds * a.Hkv, priv_per_xcd = n_priv / (4 * kXcds) * a.Hkv;
+    const int64_t grid = (coop_per_xcd + priv_per_xcd) * kXcds;
+    if (grid <= 0) return hipSuccess;
+    if (grid > INT32_MAX) return hipErrorInvalidConfiguration;
+    a.fused_coop_per_xcd = (int32_t)coop_per_xcd;
+    a.fused_priv_per_xcd = (int32_t)priv_per_xcd;
+    ProfileScope prof(kKernelFused, st);
+    if (D == 128) hipLaunchKernelGGL((attn_fused_kernel<128>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_fused_kernel<64>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_merge(int D, const MergeArgs &m, int grid, hipStream_t st) {
     if (grid <= 0) return hipSuccess;
     ProfileScope prof(kKernelMerge, st);
@@ -1036,11 +1097,17 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
         a.mode = kPlanned;
         a.members = plan->d.members;
         a.block_ids = plan->d.block_ids;
-        a.chunks = plan->d.chunks[1];
-        e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
-        if (e == hipSuccess) {
-            a.chunks = plan->d.chunks[0];
-            e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
+        if (plan->d.n_chunks[1] > 0 && plan->d.n_chunks[0] > 0 && fused_enabled()) {
+            a.chunks = plan->d.chunks[1];
+            a.chunks_priv = plan->d.chunks[0];
+            e = launch_fused(D, a, plan->d.n_chunks[1], plan->d.n_chunks[0], st);
+        } else {
+            a.chunks = plan->d.chunks[1];
+            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+            if (e == hipSuccess) {
+                a.chunks = plan->d.chunks[0];
+                e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
+            }
         }
         m.merge_slots = plan->d.merge_slots;
         m.merge_kind = plan->d.merge_kind;
@@ -1099,15 +1166,25 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         if (has_decode_rows && plan->n_slots > 0 &&
             (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < (size_t)plan->n_slots * slot_bytes))
             return GLM_ERR_WORKSPACE;
-        e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
-        if (e == hipSuccess && has_decode_rows) {
-            a.chunks = plan->d.chunks[0];
+        if (!has_decode_rows) {
+            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+        } else {
+            // (the cooperative workgroups of a prefill plan read none of the fields set here)
             a.members = plan->d.members;
             a.block_ids = plan->d.block_ids;
             a.q_row_of = cu_q_lens_dev;
             a.part_ml = (float *)workspace_dev;
             a.part_acc = a.part_ml + (size_t)plan->n_slots * (size_t)Hq * 2;
-            e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
+            if (plan->d.n_chunks[1] > 0 && fused_enabled()) {
+                a.chunks_priv = plan->d.chunks[0];
+                e = launch_fused(D, a, plan->d.n_chunks[1], plan->d.n_chunks[0], st);
+            } else {
+                e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+                if (e == hipSuccess) {
+                    a.chunks = plan->d.chunks[0];
+                    e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
+                }
+            }
             if (e == hipSuccess) {
                 MergeArgs m{};
                 m.out = (float *)out_dev;

@@ -32,7 +32,7 @@ struct DevicePlan {                   // pointers into the plan's single device 
 };
 
 // Kernel ids of glm_profile_read.
-enum KernelId : int { kKernelStream1 = 0, kKernelStream4 = 1, kKernelMerge = 2, kKernelGather = 3, kKernelFork = 4, kKernelAppend = 5, kKernelGatherTokens = 6 };
+enum KernelId : int { kKernelStream1 = 0, kKernelStream4 = 1, kKernelMerge = 2, kKernelGather = 3, kKernelFork = 4, kKernelAppend = 5, kKernelGatherTokens = 6, kKernelFused = 7 };
 
 // Brackets one kernel launch with events on its stream while profiling is enabled.
 class ProfileScope {

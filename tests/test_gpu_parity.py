@@ -1,6 +1,8 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
 seeded inputs.  Attention: max abs error <= 4e-3 (bf16 inputs, fp32 accumulate, fp32 output);
 copies: bit exact."""
+import os
+
 import numpy as np
 import pytest
 
@@ -441,3 +443,42 @@ def test_decode_wide_sharing_long_prefix_d64():
                         num_q_heads=8, num_kv_heads=2, head_dim=64)
     # with a plan the shared run goes to the cooperative launch, whose weights are plain bf16 beyond 1024 keys
     _decode_both_ways(w, "decode 160 shared rows d=64", agree=5e-4)
+
+
+def _with_env(name, value, fn):
+    old = os.environ.get(name)
+    os.environ[name] = value
+    try:
+        return fn()
+    finally:
+        if old is None:
+            os.environ.pop(name, None)
+        else:
+            os.environ[name] = old
+
+
+def test_fused_launch_equals_separate_launches():
+    """A plan with cooperative and wave-private work runs both in one launch; GLM_FUSED=0 keeps the two launches
+    apart.  Same work items, same arithmetic, same partial slots: identical bits, for decode and for a mixed batch."""
+    gu = _gu()
+    w = W.custom_decode(9400, prefix_groups=[list(range(40))], prefix_tokens=[700], suffix_tokens=[int(x) for x in range(3, 43)],
+                        num_q_heads=8, num_kv_heads=2, head_dim=128)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    kinds = {c.waves for c in plan.chunks() if c.n_mem > 0}
+    assert kinds == {1, 4}
+    fused = _with_env("GLM_FUSED", "1", lambda: dw.decode(plan=plan))
+    apart = _with_env("GLM_FUSED", "0", lambda: dw.decode(plan=plan))
+    assert np.array_equal(fused, apart)
+    ref = oracle.attention(w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale)
+    _check(fused, ref, "decode, fused launch")
+
+    wm = _mixed(9401, 128, 8, 2, q_lens=[1, 200, 1, 1, 150, 1, 0, 1], suffix=[300, 0, 5, 1000, 17, 0, 40, 47])
+    dm = gu.DeviceWorkload(wm)
+    pm = dm.make_plan()
+    assert {c.waves for c in pm.chunks() if c.n_mem > 0} == {1, 4}
+    fused = _with_env("GLM_FUSED", "1", lambda: dm.prefill(pm))
+    apart = _with_env("GLM_FUSED", "0", lambda: dm.prefill(pm))
+    assert np.array_equal(fused, apart)
+    refm = oracle.attention(wm.geom, wm.pool, wm.q, wm.block_tables, wm.seq_lens, wm.scale, cu_q_lens=wm.cu_q_lens)
+    _check(fused, refm, "mixed batch, fused launch")
