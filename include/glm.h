@@ -196,6 +196,9 @@ typedef struct {
     int32_t ids_off;  /* offset of this run's physical block ids (copied from the tables when the plan was made) */
     int32_t n_ids;    /* how many of them; blocks appended later are looked up in the live table */
     int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 128 rows; 1: one independent wave, 16 rows */
+    int32_t ids_head[4]; /* the first min(4, n_ids) of those ids again (the rest 0): a wave that has fetched its entry can
+                            request its first two tiles without a second, dependent fetch */
+    int32_t reserved[2]; /* 0; an entry is 64 bytes, one cache line */
 } glm_chunk;
 
 GLM_API int32_t glm_plan_num_chunks(const glm_plan *plan);

@@ -40,7 +40,8 @@ class glm_geom(ctypes.Structure):
 
 
 class glm_chunk(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("rep", "b0", "b1", "mem_off", "n_mem", "row0", "slot0", "ids_off", "n_ids", "waves")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("rep", "b0", "b1", "mem_off", "n_mem", "row0", "slot0", "ids_off", "n_ids", "waves")] + \
+               [("ids_head", ctypes.c_int32 * 4), ("reserved", ctypes.c_int32 * 2)]
 
 
 class GlmError(RuntimeError):

@@ -580,6 +580,8 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
         c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
         c.ids_off = __builtin_amdgcn_readfirstlane(cp->ids_off);
         c.n_ids = __builtin_amdgcn_readfirstlane(cp->n_ids);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c.ids_head[i] = __builtin_amdgcn_readfirstlane(cp->ids_head[i]);
         if (c.n_mem == 0) return;
     } else {
         int64_t I = (int64_t)L * 4 + wave;
@@ -597,6 +599,8 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
         c.slot0 = (int)r * a.n_split + s;
         c.ids_off = 0;
         c.n_ids = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c.ids_head[i] = 0;
         if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
     }
 
@@ -614,14 +618,10 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
         bf16x8 k[2][KS];
         u32x4 v[2][VPL];
     };
-    auto load_tile = [&](Tile &T, int t) {
+    auto load_blocks = [&](Tile &T, int idA, int idB) __attribute__((always_inline)) {
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb) {
-            const int rel = 2 * t + bb;
-            int id;
-            if (rel < c.n_ids) id = ids[rel];
-            else id = table[min(c.b0 + rel, last_blk)];
-            id = min(max(__builtin_amdgcn_readfirstlane(id), 0), a.num_blocks - 1);
+            const int id = min(max(__builtin_amdgcn_readfirstlane(bb ? idB : idA), 0), a.num_blocks - 1);
             const __bf16 *kb = pool_head + (int64_t)id * blk_elems;
             const __bf16 *vb = kb + (int64_t)a.Hkv * slab;
 #pragma unroll
@@ -630,14 +630,19 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
             for (int i = 0; i < VPL; ++i) T.v[bb][i] = *reinterpret_cast<const u32x4 *>(vb + v_off + 512 * i);
         }
     };
+    auto block_id = [&](int rel) -> int {
+        if (rel < c.n_ids) return ids[rel];
+        return table[min(c.b0 + rel, last_blk)];
+    };
+    auto load_tile = [&](Tile &T, int t) { load_blocks(T, block_id(2 * t), block_id(2 * t + 1)); };
 
     // Tiles that lie wholly inside the planned run are requested before anything else is known:
-    // their addresses need one dependent fetch (the id list) instead of the chain
-    // members -> lengths -> table -> K/V.
+    // their ids came with the work-list entry, so their addresses need no further fetch (instead of the
+    // chain members -> lengths -> table -> K/V).
     Tile ta, tb;
     const int early = min(c.n_ids >> 1, 2);
-    if (early >= 1) load_tile(ta, 0);
-    if (early >= 2) load_tile(tb, 1);
+    if (early >= 1) load_blocks(ta, c.ids_head[0], c.ids_head[1]);       // ids that came with the work-list entry
+    if (early >= 2) load_blocks(tb, c.ids_head[2], c.ids_head[3]);
 
     // ---- this lane's query row and the live lengths
     const int rho = c.row0 + n16;

@@ -89,6 +89,8 @@ struct Work {            // what one workgroup does: 1 cooperative chunk, or 4 w
     int32_t group;       // workgroups that stream the same K/V share a group and stay on one XCD
 };
 
+static_assert(sizeof(glm_chunk) == 64, "a work-list entry is one cache line");
+
 glm_chunk padding_chunk() {
     glm_chunk pad{};
     pad.n_mem = 0;
@@ -309,6 +311,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
                 c.slot0 = slot0;
                 c.ids_off = ids_off;
                 c.n_ids = c1 - c0;
+                for (int32_t i = 0; i < 4 && i < c.n_ids; ++i) c.ids_head[i] = p.block_ids[(size_t)ids_off + i];
                 c.waves = waves;
                 if (cooperative) {
                     const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), 32);
