@@ -1,9 +1,10 @@
 // Attention over a paged KV cache with shared prefix blocks: the streaming kernel, the
 // split-K merge kernel and the two C entry points (decode, prefill on a cached prefix).
 //
-// Two streaming kernels share one formulation (see each kernel's comment): a cooperative one
+// Two streaming bodies share one formulation (see each body's comment): a cooperative one
 // for work items with many query rows (prefill, widely shared decode runs) and a wave-private one
-// for decode items of at most 16 rows.  Everything is computed transposed so that a query row
+// for decode items of at most 16 rows.  Each has a kernel of its own, and a third kernel runs both
+// kinds of workgroups in one launch when a planned call has both.  Everything is computed transposed so that a query row
 // lives in one lane column; S^T comes out of the QK^T MFMA in exactly the register layout the
 // PV MFMA wants P^T in, and V^T is produced by the LDS transpose read (ds_read_b64_tr_b16).
 #include <algorithm>
