@@ -102,6 +102,10 @@ def test_decode_plan_covers_every_block_once_and_finds_the_tree():
             continue
         tile = 128 if c.waves == 4 else 16
         mem = members[c.mem_off:c.mem_off + c.n_mem]
+        # the entry repeats the first ids of its run (what the wave requests before it knows anything else)
+        assert c.n_ids >= 1 and list(c.reserved) == [0, 0]
+        for i in range(4):
+            assert c.ids_head[i] == (w.block_tables[c.rep, c.b0 + i] if i < c.n_ids else 0)
         lo_row, hi_row = c.row0, min(c.n_mem * G, c.row0 + tile)
         for rho in range(lo_row, hi_row):
             r = int(mem[rho // G]); gh = rho % G
