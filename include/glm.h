@@ -222,8 +222,8 @@ GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing H
  * waits for the recorded events of one kernel kind and returns their summed duration and count
  * since the last glm_profile_reset.  Kernel ids: 0 wave-private streaming attention kernel,
  * 1 cooperative attention kernel, 2 split-K merge, 3 gather, 4 fork copy, 5 K/V append,
- * 6 token gather, 7 the fused launch that runs the workgroups of 0 and 1 together (a planned call
- * that has both kinds).
+ * 6 token gather, 7 the fused launch that runs the workgroups of 0 and 1 together (a planned decode
+ * call that has both kinds).
  * Disabled by default; enabling it adds event records between kernels, so whole-call timings
  * should be taken with it off.
  */
