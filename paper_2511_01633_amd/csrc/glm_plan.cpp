@@ -542,8 +542,8 @@ int32_t glm_plan_num_members(const glm_plan *plan) { return plan ? (int32_t)plan
 int32_t glm_plan_get_members(const glm_plan *plan, int32_t *out, int32_t capacity) {
     if (!plan || !out) return 0;
     const int32_t n = std::min<int32_t>(capacity, (int32_t)plan->members.size());
-    std::memcpy(out, plan->members.data(), (size_t)n * sizeof(int32_t));
-    return n;
+    if (n > 0) std::memcpy(out, plan->members.data(), (size_t)n * sizeof(int32_t));
+    return std::max<int32_t>(n, 0);
 }
 
 int32_t glm_plan_num_shared_segments(const glm_plan *plan) { return plan ? plan->n_shared_segments : 0; }
