@@ -130,7 +130,8 @@ def bench_decode(glm, w, layers, steps, warmup):
     kern_bytes = {"attn_stream_w1": tok[1] * per_tok, "attn_stream_w4": tok[4] * per_tok,
                   "attn_stream_fused": (tok[1] + tok[4]) * per_tok}
     res = {
-        "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "layers_rotated": len(pools),
+        "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "ms_per_step_if_plan_rebuilt_every_step": ms + plan_ms,
+        "layers_rotated": len(pools),
         "unique_kv_bytes": kv_bytes, "logical_kv_bytes": w.logical_kv_bytes(), "flops": w.flops(),
         "GBps_unique": (kv_bytes + io_bytes) / ms / 1e6, "GBps_logical": (w.logical_kv_bytes() + io_bytes) / ms / 1e6,
         "tokens_per_s_per_layer": w.B / ms * 1e3, "TFLOPs": w.flops() / ms / 1e9,
