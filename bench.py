@@ -57,7 +57,7 @@ def _kv_tokens_by_kind(plan, w):
     members = plan.members()
     tok = {1: 0, 4: 0}
     for c in plan.chunks():
-        if c.n_mem == 0 or c.row0 != 0:
+        if c.n_mem == 0 or c.row0 != 0 or c.kvh > 0:
             continue
         lim = max(int(w.seq_lens[r]) for r in members[c.mem_off:c.mem_off + c.n_mem])
         end = lim if c.b1 == 2 ** 31 - 1 else min(c.b1 * 16, lim)

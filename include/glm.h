@@ -198,7 +198,10 @@ typedef struct {
     int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 128 rows; 1: one independent wave, 16 rows */
     int32_t ids_head[4]; /* the first min(4, n_ids) of those ids again (the rest 0): a wave that has fetched its entry can
                             request its first two tiles without a second, dependent fetch */
-    int32_t reserved[2]; /* 0; an entry is 64 bytes, one cache line */
+    int32_t kvh;      /* cooperative entries: the kv head this workgroup serves (one entry per head, so that the heads of
+                         one token chunk or request can run on different XCDs); -1 (wave-private entries): the launch
+                         runs the entry once for every kv head */
+    int32_t reserved; /* 0; an entry is 64 bytes, one cache line */
 } glm_chunk;
 
 GLM_API int32_t glm_plan_num_chunks(const glm_plan *plan);

@@ -42,7 +42,6 @@ struct AttnArgs {
     int32_t max_blocks, B, Hkv, Hq, G, num_blocks;
     int32_t mode;
     int32_t n_split, chunk_blocks, row_tiles;   // implicit modes
-    int32_t items_per_xcd;      // planned prefill: work items per XCD (list length / 8)
     int32_t q_rows;             // rows of Q / out (bounds the row index derived from cu_q_lens)
     float scale_log2;           // scale * log2(e)
     const int32_t *q_row_of;    // wave-private work of a mixed batch: request -> its row of Q / out (nullptr: r)
@@ -143,15 +142,14 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
     int kvh;
     const int G = a.G;
     if (a.mode == kPlanned) {
-        // workgroup L runs on XCD L % 8 and takes the (L / 8)-th (work item, kv head) pair of that XCD's
-        // list.  Decode: kv head fastest (row tiles of one chunk are neighbours in the list and meet in
-        // L2).  Prefill: kv head slowest, so that the workgroups in flight on an XCD are the row tiles of
-        // few (request, kv head) streams and each stream's K/V is pulled into that L2 once.
+        // workgroup L runs on XCD L % 8 and takes the (L / 8)-th entry of that XCD's list.  An entry names
+        // its kv head; the row tiles of one (token chunk or request, kv head) are neighbours in the list, so
+        // the workgroups in flight on an XCD are the row tiles of few K/V streams and each stream is pulled
+        // into that L2 once.
         const int x = L % kXcds, k = L / kXcds;
-        int ci;
-        if (a.cu_q_lens) { kvh = k / a.items_per_xcd; ci = k % a.items_per_xcd; }
-        else { kvh = k % a.Hkv; ci = k / a.Hkv; }
+        const int ci = k;
         const glm_chunk *cp = chunks + (ci * kXcds + x);
+        kvh = min(max(__builtin_amdgcn_readfirstlane(cp->kvh), 0), a.Hkv - 1);
         c.rep = __builtin_amdgcn_readfirstlane(cp->rep);
         c.b0 = __builtin_amdgcn_readfirstlane(cp->b0);
         c.b1 = __builtin_amdgcn_readfirstlane(cp->b1);
@@ -977,7 +975,7 @@ bool fused_enabled() {
 
 // a: cooperative list in a.chunks (n_coop entries), wave-private list in a.chunks_priv (n_priv entries)
 hipError_t launch_fused(int D, AttnArgs &a, int64_t n_coop, int64_t n_priv, hipStream_t st) {
-    const int64_t coop_per_xcd = n_coop / kXcds * a.Hkv, priv_per_xcd = n_priv / (4 * kXcds) * a.Hkv;
+    const int64_t coop_per_xcd = n_coop / kXcds, priv_per_xcd = n_priv / (4 * kXcds) * a.Hkv;
     const int64_t grid = (coop_per_xcd + priv_per_xcd) * kXcds;
     if (grid <= 0) return hipSuccess;
     if (grid > INT32_MAX) return hipErrorInvalidConfiguration;
@@ -1109,7 +1107,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
             e = launch_fused(D, a, plan->d.n_chunks[1], plan->d.n_chunks[0], st);
         } else {
             a.chunks = plan->d.chunks[1];
-            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1], st);
             if (e == hipSuccess) {
                 a.chunks = plan->d.chunks[0];
                 e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
@@ -1165,7 +1163,6 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
     if (plan) {
         a.mode = kPlanned;
         a.chunks = plan->d.chunks[1];
-        a.items_per_xcd = std::max(1, plan->d.n_chunks[1] / kXcds);
         // a mixed batch: its one-token requests run as split-K items of the wave-private launch and are merged
         const bool has_decode_rows = plan->d.n_chunks[0] > 0;
         const size_t slot_bytes = (size_t)Hq * (size_t)(D + 2) * sizeof(float);
@@ -1173,7 +1170,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
             (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < (size_t)plan->n_slots * slot_bytes))
             return GLM_ERR_WORKSPACE;
         if (!has_decode_rows) {
-            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1], st);
         } else {
             // (the cooperative workgroups of a prefill plan read none of the fields set here)
             a.members = plan->d.members;
@@ -1184,7 +1181,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
             // Two launches, not the fused one: the cooperative workgroups write the prefill rows' output
             // (tens of MB), and its way out of L2 at the end of their launch is hidden behind the wave-private
             // launch; behind a fused launch it delays the merge (measured: 218 against 223 us per call).
-            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1] * Hkv, st);
+            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1], st);
             if (e == hipSuccess) {
                 a.chunks = plan->d.chunks[0];
                 e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);

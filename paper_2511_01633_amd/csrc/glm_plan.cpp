@@ -95,6 +95,7 @@ glm_chunk padding_chunk() {
     glm_chunk pad{};
     pad.n_mem = 0;
     pad.slot0 = -1;
+    pad.kvh = -1;
     return pad;
 }
 
@@ -250,7 +251,10 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
         if (count_items(cb_family, cb_single) <= target) break;
     }
     if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb_family = cb_single = std::max(1, forced);
-    const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 3);
+    // Cooperative runs are cut only as far as one round of the chip's 512 workgroup slots needs: every chunk
+    // costs each member a partial result, and the slots a short round leaves empty are taken by the
+    // wave-private workgroups of the same launch.
+    const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 2);
     int32_t cb_coop = (int32_t)std::max<int64_t>(env_int("GLM_PLAN_COOP_MIN_CHUNK_BLOCKS", 16), units_coop * p.g.num_kv_heads / std::max(1, target_coop));
     cb_coop = (cb_coop + 1) & ~1;
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
@@ -313,15 +317,22 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
                 c.n_ids = c1 - c0;
                 for (int32_t i = 0; i < 4 && i < c.n_ids; ++i) c.ids_head[i] = p.block_ids[(size_t)ids_off + i];
                 c.waves = waves;
+                c.kvh = -1;
                 if (cooperative) {
+                    // one entry per kv head: the row tiles of one (token chunk, kv head) stream the same K/V and
+                    // stay on one XCD, different heads share nothing and may go to different XCDs (a widely
+                    // shared prefix cut into fewer chunks than there are XCDs would otherwise leave XCDs idle)
                     const int64_t tiles_here = ceil_div(std::min<int64_t>(tile_rows, rows - row0), 32);
-                    Work w{};
-                    w.c[0] = c;
-                    w.n = 1;
-                    w.cost = (int64_t)(c1 - c0) * (4 + tiles_here);
-                    w.bytes = row0 == 0 ? c1 - c0 : 0;
-                    w.group = group;
-                    coop.push_back(w);
+                    for (int32_t kvh = 0; kvh < p.g.num_kv_heads; ++kvh) {
+                        Work w{};
+                        w.c[0] = c;
+                        w.c[0].kvh = kvh;
+                        w.n = 1;
+                        w.cost = (int64_t)(c1 - c0) * (4 + tiles_here);
+                        w.bytes = row0 == 0 ? c1 - c0 : 0;
+                        w.group = group * p.g.num_kv_heads + kvh;
+                        coop.push_back(w);
+                    }
                 } else if (rows > kRowsPerWave) {
                     families.push_back({c, (int64_t)(c1 - c0), row0 == 0});
                 } else {
@@ -382,13 +393,16 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
             c.waves = kBigWaves;
             const int64_t last_pos = std::min<int64_t>(rows, row0 + tile_rows) - 1;
             const int64_t visible = ctx + last_pos / G + 1;
-            Work wk{};
-            wk.c[0] = c;
-            wk.n = 1;
-            wk.cost = ceil_div(visible, kBlockSize);
-            wk.bytes = row0 == 0 ? wk.cost : 0;
-            wk.group = r;                       // the tiles of one request walk the same blocks
-            work.push_back(wk);
+            for (int32_t kvh = 0; kvh < p.g.num_kv_heads; ++kvh) {
+                Work wk{};
+                wk.c[0] = c;
+                wk.c[0].kvh = kvh;
+                wk.n = 1;
+                wk.cost = ceil_div(visible, kBlockSize);
+                wk.bytes = row0 == 0 ? wk.cost : 0;
+                wk.group = r * p.g.num_kv_heads + kvh;      // the tiles of one (request, kv head) walk the same K/V
+                work.push_back(wk);
+            }
         }
     }
     p.chunks[0].clear();

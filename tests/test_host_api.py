@@ -103,7 +103,10 @@ def test_decode_plan_covers_every_block_once_and_finds_the_tree():
         tile = 128 if c.waves == 4 else 16
         mem = members[c.mem_off:c.mem_off + c.n_mem]
         # the entry repeats the first ids of its run (what the wave requests before it knows anything else)
-        assert c.n_ids >= 1 and list(c.reserved) == [0, 0]
+        assert c.n_ids >= 1 and c.reserved == 0
+        assert (0 <= c.kvh < w.geom.num_kv_heads) if c.waves == 4 else c.kvh == -1
+        if c.kvh > 0:
+            continue                       # the same rows and blocks as the entry of kv head 0
         for i in range(4):
             assert c.ids_head[i] == (w.block_tables[c.rep, c.b0 + i] if i < c.n_ids else 0)
         lo_row, hi_row = c.row0, min(c.n_mem * G, c.row0 + tile)
@@ -147,11 +150,11 @@ def test_prefill_plan_tiles_every_row():
     for c in plan.chunks():
         if c.n_mem == 0:
             continue
-        assert c.waves == 4 and c.slot0 == -1 and c.n_mem == q_lens[c.rep]
+        assert c.waves == 4 and c.slot0 == -1 and c.n_mem == q_lens[c.rep] and 0 <= c.kvh < 2
         for rho in range(c.row0, min(c.n_mem * 4, c.row0 + 128)):
-            rows[(c.rep, rho)] = rows.get((c.rep, rho), 0) + 1
-    assert all(v == 1 for v in rows.values())
-    assert len(rows) == int(q_lens.sum()) * 4
+            rows[(c.rep, c.kvh, rho)] = rows.get((c.rep, c.kvh, rho), 0) + 1
+    assert all(v == 1 for v in rows.values())                  # every (request, kv head, row) in exactly one tile
+    assert len(rows) == int(q_lens.sum()) * 4 * 2
     assert plan.workspace_bytes <= 256
 
 
