@@ -159,15 +159,15 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
         c.slot0 = __builtin_amdgcn_readfirstlane(cp->slot0);
         if (c.n_mem == 0) return;
     } else {
-        // prefill without a plan: XCD x takes the requests x, x+8, ..; on it kv head is the slowest
-        // index, then the request, then the row tile (same reason as above)
+        // prefill without a plan: XCD x takes the (request, kv head) pairs x, x+8, .. (kv head fastest, so
+        // that even a single request occupies every XCD), one pair after the other, its row tiles together
         const int x = L % kXcds;
         int k = L / kXcds;
         const int t = k % a.row_tiles; k /= a.row_tiles;
-        const int per_xcd = (a.B + kXcds - 1) / kXcds;
-        const int r = x + kXcds * (k % per_xcd);
-        kvh = k / per_xcd;
-        if (r >= a.B) return;
+        const int64_t pair = x + (int64_t)kXcds * k;
+        if (pair >= (int64_t)a.B * a.Hkv) return;
+        const int r = (int)(pair / a.Hkv);
+        kvh = (int)(pair % a.Hkv);
         c.rep = r;
         c.b0 = 0;
         c.b1 = INT32_MAX;
@@ -1206,7 +1206,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         if (max_q_len == 0) return GLM_OK;
         a.mode = kImplicitPrefill;
         const int64_t tiles = ((int64_t)max_q_len * G + kCoopRows - 1) / kCoopRows;
-        const int64_t grid = tiles * (((int64_t)B + kXcds - 1) / kXcds) * kXcds * Hkv;
+        const int64_t grid = tiles * (((int64_t)B * Hkv + kXcds - 1) / kXcds) * kXcds;
         if (grid > INT32_MAX) return GLM_ERR_GEOM;
         a.row_tiles = (int32_t)tiles;
         e = launch_coop(D, a, grid, st);
