@@ -145,7 +145,9 @@ std::vector<glm_chunk> deal_to_xcds(std::vector<Work> &w, int per_group) {
         }
         load_cost[best] += g.cost;
         load_bytes[best] += g.bytes;
-        for (size_t i : g.items) per[best].push_back(i);      // already in descending cost order
+        std::vector<size_t> items = g.items;                  // the group's costly workgroups first
+        std::stable_sort(items.begin(), items.end(), [&](size_t a, size_t b) { return w[a].cost > w[b].cost; });
+        for (size_t i : items) per[best].push_back(i);
     }
     size_t longest = 0;
     for (auto &v : per) longest = std::max(longest, v.size());
