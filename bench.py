@@ -123,6 +123,14 @@ def bench_decode(glm, w, layers, steps, warmup):
 
     ms = _time_steps(step, steps, warmup)
     kt = _kernel_times(glm, step, min(steps, 64))
+    # the same call without a plan: every request streams its own K/V, shared blocks once per request
+    ws_np = torch.empty(glm.glm_attn_workspace_bytes(g, w.B, 0, int(w.seq_lens.max())), dtype=torch.uint8, device="cuda")
+
+    def step_np(i):
+        glm.glm_attn_decode(g, pools[i % len(pools)], q, out, tables, w.max_blocks, lens, w.B, w.scale, None, ws_np)
+
+    ms_np = _time_steps(step_np, max(5, steps // 8), max(2, warmup // 4))
+    del ws_np
     kv_bytes = w.unique_kv_bytes()
     io_bytes = w.q.nbytes + out.numel() * 4
     tok = _kv_tokens_by_kind(plan, w)
@@ -131,6 +139,7 @@ def bench_decode(glm, w, layers, steps, warmup):
                   "attn_stream_fused": (tok[1] + tok[4]) * per_tok}
     res = {
         "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "ms_per_step_if_plan_rebuilt_every_step": ms + plan_ms,
+        "ms_per_step_without_plan": ms_np, "speedup_from_streaming_shared_blocks_once": ms_np / ms,
         "layers_rotated": len(pools),
         "unique_kv_bytes": kv_bytes, "logical_kv_bytes": w.logical_kv_bytes(), "flops": w.flops(),
         "GBps_unique": (kv_bytes + io_bytes) / ms / 1e6, "GBps_logical": (w.logical_kv_bytes() + io_bytes) / ms / 1e6,
