@@ -219,6 +219,16 @@ def test_prefill_small_shapes(hq, hkv, d):
     _prefill_both_ways(w, "prefill %d/%d d%d" % (hq, hkv, d))
 
 
+@pytest.mark.parametrize("B,hq,hkv,d", [(1, 32, 8, 128), (3, 8, 1, 64), (5, 12, 4, 128), (9, 16, 8, 64)])
+def test_prefill_fewer_or_more_requests_than_xcds(B, hq, hkv, d):
+    """(request, kv head) groups are dealt over the 8 XCDs, with a plan and without: every pair must be served exactly
+    once whatever B * Hkv is against 8, with several row tiles per request."""
+    q_lens = [150 + 40 * i for i in range(B)]
+    w = W.custom_prefill(3200 + B, prefix_groups=[list(range(B))], prefix_tokens=[100], q_lens=q_lens, num_q_heads=hq,
+                         num_kv_heads=hkv, head_dim=d)
+    _prefill_both_ways(w, "prefill B=%d %d/%d d%d" % (B, hq, hkv, d))
+
+
 def test_prefill_without_any_cached_prefix_and_row_vs_decode():
     w = W.custom_prefill(3100, prefix_groups=[], prefix_tokens=[], q_lens=[4, 1, 37], num_q_heads=8, num_kv_heads=2,
                          head_dim=128)
