@@ -257,7 +257,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     // costs each member a partial result, and the slots a short round leaves empty are taken by the
     // wave-private workgroups of the same launch.
     const int target_coop = env_int("GLM_PLAN_TARGET_WORKGROUPS", 256 * 2);
-    int32_t cb_coop = (int32_t)std::max<int64_t>(env_int("GLM_PLAN_COOP_MIN_CHUNK_BLOCKS", 16), units_coop * p.g.num_kv_heads / std::max(1, target_coop));
+    int32_t cb_coop = (int32_t)std::max<int64_t>(env_int("GLM_PLAN_COOP_MIN_CHUNK_BLOCKS", 32), units_coop * p.g.num_kv_heads / std::max(1, target_coop));
     cb_coop = (cb_coop + 1) & ~1;
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
     auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };
