@@ -124,6 +124,28 @@ def test_decode_plan_covers_every_block_once_and_finds_the_tree():
     assert len(seen) == sum(-(-int(L) // 16) for L in w.seq_lens) * G
 
 
+def test_cooperative_work_is_spread_over_all_xcds():
+    """Workgroup i of a launch runs on XCD i % 8.  A widely shared run cut into fewer chunks than there are XCDs must
+    still reach all of them (its kv heads are separate entries), and so must a prefill batch of fewer requests than
+    XCDs."""
+    w = W.tree_decode_70b()
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    coop = [c for c in plan.chunks() if c.waves == 4]
+    assert len(coop) % 8 == 0
+    load = [0] * 8
+    for i, c in enumerate(coop):
+        if c.n_mem:
+            load[i % 8] += c.n_ids
+    assert min(load) > 0 and max(load) <= 1.1 * min(load), load
+    assert len({(c.b0, c.kvh) for c in coop if c.n_mem and c.b0 == 0}) == w.geom.num_kv_heads
+
+    wp = W.custom_prefill(5, prefix_groups=[[0]], prefix_tokens=[512], q_lens=[1024], num_q_heads=32, num_kv_heads=8, head_dim=128)
+    pp = glm.glm_plan_create_host(wp.geom, wp.block_tables, wp.max_blocks, wp.seq_lens, wp.q_lens, wp.B)
+    tiles = [c for c in pp.chunks() if c.waves == 4]
+    per_xcd = [sum(1 for i, c in enumerate(tiles) if c.n_mem and i % 8 == x) for x in range(8)]
+    assert min(per_xcd) == max(per_xcd) == 1024 * 4 // 128, per_xcd          # one kv head's row tiles per XCD
+
+
 def test_plan_handles_partial_sharing_and_unequal_lengths():
     # request 1 ends inside the run shared with request 0; request 2 shares only the first block
     tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)
