@@ -47,6 +47,7 @@ struct AttnArgs {
     const int32_t *q_row_of;    // wave-private work of a mixed batch: request -> its row of Q / out (nullptr: r)
     const glm_chunk *chunks_priv;   // fused launch: the wave-private list (chunks is the cooperative one)
     int32_t fused_coop_per_xcd, fused_priv_per_xcd;   // fused launch: workgroups of each kind per XCD
+    int32_t fused_coop_first;   // fused launch: all cooperative workgroups ahead of the wave-private ones
 };
 
 struct MergeArgs {
@@ -830,14 +831,20 @@ __global__ void __launch_bounds__(256, 2) attn_private_kernel(const AttnArgs a) 
 // matrix units, the wave-private ones by HBM; launched one after the other each leaves the other's
 // resource idle, and the first launch's last, partly filled round of workgroups leaves CUs idle as well.
 // Here the k-th workgroup of an XCD is cooperative or wave-private such that both lists are used up at the
-// same rate.  Workgroup L still runs on XCD L % 8 and takes its XCD's next entry of its kind, so the
-// per-XCD balance and order of either list are kept.
+// same rate; if the cooperative list is short against the other (half as long or less), its workgroups - the
+// longer-running kind - all go first instead.  Workgroup L still runs on XCD L % 8 and takes its XCD's
+// next entry of its kind, so the per-XCD balance and order of either list are kept.
 template <int D>
 __global__ void __launch_bounds__(256, 2) attn_fused_kernel(const AttnArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[stream_smem_bytes<D>()];
     const int L = blockIdx.x;
     const int x = L % kXcds, k = L / kXcds;
     const int64_t nc = a.fused_coop_per_xcd, tot = nc + a.fused_priv_per_xcd;
+    if (a.fused_coop_first) {
+        if (k < nc) attn_coop_body<D>(a, a.chunks, k * kXcds + x, smem);
+        else attn_private_body<D>(a, a.chunks_priv, (int)(k - nc) * kXcds + x, smem);
+        return;
+    }
     const int before = (int)(k * nc / tot);                 // cooperative workgroups among this XCD's first k
     if ((int)((k + 1) * nc / tot) > before) attn_coop_body<D>(a, a.chunks, before * kXcds + x, smem);
     else attn_private_body<D>(a, a.chunks_priv, (k - before) * kXcds + x, smem);
@@ -981,6 +988,7 @@ hipError_t launch_fused(int D, AttnArgs &a, int64_t n_coop, int64_t n_priv, hipS
     if (grid > INT32_MAX) return hipErrorInvalidConfiguration;
     a.fused_coop_per_xcd = (int32_t)coop_per_xcd;
     a.fused_priv_per_xcd = (int32_t)priv_per_xcd;
+    a.fused_coop_first = coop_per_xcd * 2 <= priv_per_xcd;
     ProfileScope prof(kKernelFused, st);
     if (D == 128) hipLaunchKernelGGL((attn_fused_kernel<128>), dim3((unsigned)grid), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_fused_kernel<64>), dim3((unsigned)grid), dim3(256), 0, st, a);
