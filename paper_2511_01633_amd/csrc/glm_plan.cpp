@@ -233,7 +233,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     // shared by 17..127 rows (the tiles stream the same K/V, three of four find it in L2) and of
     // 1.16 (n + 3) when it streams alone.  Both chunk lengths are derived from one duration: the
     // shortest for which the launch still is one round.
-    const int min_cb = env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8), max_cb = env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 64);
+    const int min_cb = env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8), max_cb = env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 128);
     const int target = env_int("GLM_PLAN_TARGET_ITEMS", 2040);
     auto clamp_cb = [&](int tiles) { return std::min(std::max(2 * tiles, min_cb), max_cb); };
     auto count_items = [&](int32_t cb_fam, int32_t cb_one) {
