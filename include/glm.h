@@ -192,7 +192,8 @@ typedef struct {
     int32_t mem_off;  /* decode: offset of the member list; prefill: unused */
     int32_t n_mem;    /* decode: member requests; prefill: new tokens of rep; 0 = padding entry */
     int32_t row0;     /* first of the n_mem*(Hq/Hkv) rows this workgroup handles */
-    int32_t slot0;    /* first partial-result slot, or -1: writes the final output itself */
+    int32_t slot0;    /* where the members' partial-result slots are listed in the plan (member i: entry slot0 + i),
+                         or -1: writes the final output itself */
     int32_t ids_off;  /* offset of this run's physical block ids (copied from the tables when the plan was made) */
     int32_t n_ids;    /* how many of them; blocks appended later are looked up in the live table */
     int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 128 rows; 1: one independent wave, 16 rows */

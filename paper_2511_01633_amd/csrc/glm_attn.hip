@@ -36,6 +36,7 @@ struct AttnArgs {
     const int32_t *cu_q_lens;   // nullptr: decode
     const glm_chunk *chunks;    // planned mode
     const int32_t *members;     // planned decode
+    const int32_t *slot_ids;    // planned decode: member mi of a chunk writes its partial to slot slot_ids[slot0 + mi]
     const int32_t *block_ids;   // planned decode: physical ids of each item's run
     float *part_ml;             // [slot][Hq][2]  (running max in log2 units, sum)
     float *part_acc;            // [slot][Hq][D]
@@ -55,11 +56,12 @@ struct MergeArgs {
     const float *part_acc;
     float *out;
     const int32_t *seq_lens;
-    const int32_t *merge_slots, *merge_kind, *merge_cnt;   // nullptr: implicit
+    const int32_t *merge_kind, *merge_cnt;   // nullptr: implicit (request r then owns slots r * n_split ..)
     int32_t merge_stride;
     int32_t Hq, max_blocks, n_split, chunk_blocks;
     const int32_t *q_row_of;    // mixed batch: request -> its row of out (nullptr: r)
     int32_t q_rows;
+    int32_t have_partials;      // the workspace holds partial slots (0: every request wrote its output itself)
 };
 
 __device__ __forceinline__ int wave_max(int v) {
@@ -185,6 +187,7 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
     const int mi = rho / G, gh = rho - mi * G;
     int64_t q_row = 0;
     int limit = 0;
+    int part_slot = 0;
     if (valid) {
         if (a.cu_q_lens) {
             const int ctx = a.seq_lens[c.rep] - c.n_mem;
@@ -195,6 +198,8 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
             q_row = r;
             limit = a.seq_lens[r];
         }
+        // where this row's partial result goes (fetched now, beside the member list, and kept in a register)
+        if (c.slot0 >= 0) part_slot = (c.mem_off >= 0 && a.slot_ids) ? a.slot_ids[c.slot0 + mi] : c.slot0 + mi;
     }
     const int head = kvh * G + gh;
 
@@ -512,7 +517,7 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
     // acc[dt][i] is row m = 8*(i/4) + 4*h2 + i%4 of O^T tile dt, which is d = 16*dt + m for m < 16 and
     // d = D/2 + 16*dt + m - 16 otherwise (see v_rd)
     if (c.slot0 >= 0) {
-        const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
+        const int64_t slot = (int64_t)part_slot * a.Hq + head;
         if (h2 == 0) {
             a.part_ml[slot * 2] = m_run;
             a.part_ml[slot * 2 + 1] = l_run;
@@ -650,10 +655,13 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
     const int mi = rho / G, gh = rho - mi * G;
     int64_t q_row = 0;
     int limit = 0;
+    int part_slot = 0;
     if (valid) {
         const int r = c.mem_off < 0 ? c.rep : a.members[c.mem_off + mi];
         q_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
         limit = a.seq_lens[r];
+        // where this row's partial result goes (fetched now, beside the member list, and kept in a register)
+        if (c.slot0 >= 0) part_slot = (c.mem_off >= 0 && a.slot_ids) ? a.slot_ids[c.slot0 + mi] : c.slot0 + mi;
     }
     const int head = kvh * G + gh;
     int wv_lim = __builtin_amdgcn_readfirstlane(wave_max(limit));
@@ -799,7 +807,7 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
     l_run += __shfl_xor(l_run, 32);
     if (!valid) return;
     if (c.slot0 >= 0) {
-        const int64_t slot = ((int64_t)c.slot0 + mi) * a.Hq + head;
+        const int64_t slot = (int64_t)part_slot * a.Hq + head;
         if (g4 == 0) {
             a.part_ml[slot * 2] = m_run;
             a.part_ml[slot * 2 + 1] = l_run;
@@ -859,55 +867,60 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
     constexpr int E = D / 64;
     const int64_t out_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
     float *dst = a.out + (out_row * a.Hq + h) * D + lane * E;
-    int n, first = 0;
-    const int32_t *slots = nullptr;
+    // Request r owns the partial slots r * stride .. r * stride + n - 1, in merge order, so every address is
+    // known from r alone: the (m, l) pairs of the first 64 partials and the first accumulator rows are
+    // requested together with the count n, before n is known (slots at or beyond n hold stale data that is
+    // never used: they are masked by selects, not by multiplication).
+    const int stride = a.merge_kind ? a.merge_stride : a.n_split;
+    const int64_t row0 = ((int64_t)r * stride) * a.Hq + h;       // partial row of slot r * stride; next slot: + Hq
+    auto fetch = [&](int i0, int cnt, float (&v)[8][E]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = min(i0 + j, cnt - 1);
+            const float *src = a.part_acc + (row0 + (int64_t)i * a.Hq) * D + lane * E;
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[j][e] = src[e];
+        }
+    };
+    float my_m = -INFINITY, my_l = 0.f;
+    float v[8][E];
+    if (a.have_partials) {          // (without partial slots there is no workspace to read, and nothing to merge)
+        if (lane < stride) {
+            my_m = a.part_ml[(row0 + (int64_t)lane * a.Hq) * 2];
+            my_l = a.part_ml[(row0 + (int64_t)lane * a.Hq) * 2 + 1];
+        }
+        fetch(0, min(stride, 64), v);
+    }
+    int n;
     if (a.merge_kind) {
-        // the slot list sits at a fixed stride, so its fetch does not wait for the count
-        slots = a.merge_slots + (int64_t)r * a.merge_stride;
-        const int first_slot = lane < a.merge_stride ? slots[lane] : 0;
         const int kind = a.merge_kind[r];
-        n = a.merge_cnt[r];
+        n = min(a.merge_cnt[r], stride);
         if (kind == kMergeDirect) return;
         if (kind == kMergeZero) {
 #pragma unroll
             for (int e = 0; e < E; ++e) dst[e] = 0.f;
             return;
         }
-        first = first_slot;   // lane's slot of the first group of 64
     } else {
         const int nb = min((a.seq_lens[r] + kBlockSize - 1) / kBlockSize, a.max_blocks);
         n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
-        first = r * a.n_split + lane;
     }
     float M = -INFINITY, l = 0.f, o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
-    // 64 partials at a time: lane i fetches (m, l) of partial i, so the fetches overlap; the first
-    // accumulator rows are requested before the (m, l) values are needed.  The running maximum M
-    // carries over between groups and the order of accumulation is fixed.
+    // 64 partials at a time: lane i holds (m, l) of partial i.  The running maximum M carries over between
+    // groups and the order of accumulation is fixed.
     for (int base = 0; base < n; base += 64) {
         const int cnt = min(64, n - base);
-        int64_t my_slot = 0;
-        float my_m = -INFINITY, my_l = 0.f;
-        if (lane < cnt) {
-            const int sl = base == 0 ? first : (slots ? slots[base + lane] : r * a.n_split + base + lane);
-            my_slot = (int64_t)sl * a.Hq + h;
-            my_m = a.part_ml[my_slot * 2];
-            my_l = a.part_ml[my_slot * 2 + 1];
-        }
-        const int lo32 = (int)(my_slot & 0xffffffff), hi32 = (int)(my_slot >> 32);
-        auto fetch = [&](int i0, float (&v)[8][E]) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int i = min(i0 + j, cnt - 1);
-                const int64_t s = ((int64_t)__shfl(hi32, i) << 32) | (uint32_t)__shfl(lo32, i);
-                const float *src = a.part_acc + s * D + lane * E;
-#pragma unroll
-                for (int e = 0; e < E; ++e) v[j][e] = src[e];
+        if (base > 0) {
+            my_m = -INFINITY; my_l = 0.f;
+            if (lane < cnt) {
+                my_m = a.part_ml[(row0 + (int64_t)(base + lane) * a.Hq) * 2];
+                my_l = a.part_ml[(row0 + (int64_t)(base + lane) * a.Hq) * 2 + 1];
             }
-        };
-        float v[8][E];
-        fetch(0, v);
+        } else if (lane >= cnt) {
+            my_m = -INFINITY; my_l = 0.f;
+        }
         float gm = my_m;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off));
@@ -924,7 +937,7 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
         for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
         l += lw;
         for (int i0 = 0; i0 < cnt; i0 += 8) {               // 8 independent fetches in flight at a time
-            if (i0 > 0) fetch(i0, v);
+            if (base > 0 || i0 > 0) fetch(base + i0, base + cnt, v);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float w = (i0 + j < cnt) ? __shfl(my_w, min(i0 + j, cnt - 1)) : 0.f;
@@ -1100,6 +1113,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
     a.part_acc = a.part_ml + n_slots * (size_t)Hq * 2;
     m.part_ml = a.part_ml;
     m.part_acc = a.part_acc;
+    m.have_partials = n_slots > 0;
 
     if (validate_enabled())
         if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, nullptr, B, 0, st)) return v;
@@ -1108,6 +1122,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
     if (plan) {
         a.mode = kPlanned;
         a.members = plan->d.members;
+        a.slot_ids = plan->d.slot_ids;
         a.block_ids = plan->d.block_ids;
         if (plan->d.n_chunks[1] > 0 && plan->d.n_chunks[0] > 0 && fused_enabled()) {
             a.chunks = plan->d.chunks[1];
@@ -1121,7 +1136,6 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
                 e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
             }
         }
-        m.merge_slots = plan->d.merge_slots;
         m.merge_kind = plan->d.merge_kind;
         m.merge_cnt = plan->d.merge_cnt;
         m.merge_stride = plan->merge_stride;
@@ -1182,6 +1196,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         } else {
             // (the cooperative workgroups of a prefill plan read none of the fields set here)
             a.members = plan->d.members;
+            a.slot_ids = plan->d.slot_ids;
             a.block_ids = plan->d.block_ids;
             a.q_row_of = cu_q_lens_dev;
             a.part_ml = (float *)workspace_dev;
@@ -1201,7 +1216,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
                 m.Hq = Hq; m.max_blocks = max_blocks;
                 m.part_ml = a.part_ml;
                 m.part_acc = a.part_acc;
-                m.merge_slots = plan->d.merge_slots;
+                m.have_partials = plan->n_slots > 0;
                 m.merge_kind = plan->d.merge_kind;
                 m.merge_cnt = plan->d.merge_cnt;
                 m.merge_stride = plan->merge_stride;

@@ -25,8 +25,7 @@ struct DevicePlan {                   // pointers into the plan's single device 
     int32_t n_chunks[2] = {0, 0};     // multiples of kXcds (padded with n_mem == 0 entries)
     const int32_t *members = nullptr;
     const int32_t *block_ids = nullptr;   // physical ids of every planned run, see glm_chunk::ids_off
-    const int32_t *merge_off = nullptr;   // [B+1], = r * merge_stride
-    const int32_t *merge_slots = nullptr; // member-slot indices, merge_stride per request
+    const int32_t *slot_ids = nullptr;    // where a member of a chunk writes its partial: slot_ids[chunk.slot0 + mi]
     const int32_t *merge_cnt = nullptr;   // [B] partials of each request
     const int32_t *merge_kind = nullptr;  // [B]
 };
@@ -59,9 +58,9 @@ struct glm_plan {
     int32_t B = 0, max_blocks = 0;
     int32_t kind = glm::kDecode;
     std::vector<glm_chunk> chunks[2];
-    std::vector<int32_t> members, block_ids, merge_off, merge_slots, merge_kind, merge_cnt;
-    int32_t merge_stride = 1;
-    int32_t n_slots = 0;              // member slots; a slot holds Hq partial rows
+    std::vector<int32_t> members, block_ids, slot_ids, merge_kind, merge_cnt;
+    int32_t merge_stride = 1;         // partial slots per request: request r owns slots r * stride .. + merge_cnt[r] - 1
+    int32_t n_slots = 0;              // B * merge_stride (0 if nothing is merged); a slot holds Hq partial rows
     int32_t n_shared_segments = 0;
     int64_t shared_blocks = 0;
     void *dev = nullptr;              // device allocation, nullptr for host-only plans

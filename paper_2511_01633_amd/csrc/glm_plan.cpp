@@ -262,13 +262,14 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
     auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };
 
-    std::vector<std::vector<int32_t>> per_req(B);
+    std::vector<int32_t> n_partials(B, 0);      // partial results of each request so far
     std::vector<Work> coop;
     std::vector<Item> families, singles;
     int32_t n_groups = 0;
     p.members.clear();
     p.block_ids.clear();
     p.n_slots = 0;
+    p.slot_ids.clear();
     p.n_shared_segments = 0;
     p.shared_blocks = 0;
     std::vector<int32_t> n_chunks_of(B, 0);
@@ -277,6 +278,11 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
         const int32_t nc = ceil_div(len, chunk_blocks((int64_t)s.members.size() * G));
         for (int32_t r : s.members) n_chunks_of[r] += nc;
     }
+    // A request's partial results get the slots r * stride + 0, 1, .. in the order its chunks are made (the merge
+    // order), so the merging wave needs no list of slots: it knows all its addresses from r alone.
+    int32_t stride = 1;
+    for (int32_t r = 0; r < B; ++r) stride = std::max(stride, n_chunks_of[r]);
+    p.merge_stride = stride;
     for (auto &s : segs) {
         const int32_t nm = (int32_t)s.members.size();
         if (nm >= 2) { ++p.n_shared_segments; p.shared_blocks += s.b1 - s.b0; }
@@ -299,9 +305,11 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
             const bool direct = (nm == 1 && n_chunks_of[s.members[0]] == 1 && last && k == 0);
             int32_t slot0 = -1;
             if (!direct) {
-                slot0 = p.n_slots;
-                p.n_slots += nm;
-                for (int32_t mi = 0; mi < nm; ++mi) per_req[s.members[mi]].push_back(slot0 + mi);
+                slot0 = (int32_t)p.slot_ids.size();
+                for (int32_t mi = 0; mi < nm; ++mi) {
+                    const int32_t r = s.members[mi];
+                    p.slot_ids.push_back(r * stride + n_partials[r]++);
+                }
             }
             const int32_t group = n_groups++;
             const int32_t ids_off = (int32_t)p.block_ids.size();
@@ -344,24 +352,15 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
             if (last) break;
         }
     }
-    // merge lists with a fixed stride per request, so that a merging wave can fetch its slot list and
-    // its count in parallel (merge_off[r] = r * stride is kept for inspection)
-    size_t stride = 1;
-    for (int32_t r = 0; r < B; ++r) stride = std::max(stride, per_req[r].size());
-    p.merge_stride = (int32_t)stride;
-    p.merge_off.assign(B + 1, 0);
+    p.n_slots = p.slot_ids.empty() ? 0 : B * stride;
     p.merge_cnt.assign(B, 0);
     p.merge_kind.assign(B, kMergeList);
-    p.merge_slots.assign((size_t)B * stride, 0);
     for (int32_t r = 0; r < B; ++r) {
-        p.merge_off[r] = (int32_t)(r * stride);
-        p.merge_cnt[r] = (int32_t)per_req[r].size();
+        p.merge_cnt[r] = n_partials[r];
         if (!planned[r]) p.merge_kind[r] = kMergeDirect;          // somebody else writes (or there is nothing to write)
         else if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
-        else if (per_req[r].empty()) p.merge_kind[r] = kMergeDirect;
-        std::copy(per_req[r].begin(), per_req[r].end(), p.merge_slots.begin() + (size_t)r * stride);
+        else if (n_partials[r] == 0) p.merge_kind[r] = kMergeDirect;
     }
-    p.merge_off[B] = (int32_t)((size_t)B * stride);
     std::vector<Work> quads = pack_quads(families, singles);
     p.chunks[0] = deal_to_xcds(quads, 4);
     if (!subset) p.chunks[1] = deal_to_xcds(coop, 1);
@@ -410,8 +409,7 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
     p.chunks[0].clear();
     p.chunks[1] = deal_to_xcds(work, 1);
     p.members.clear();
-    p.merge_off.assign(B + 1, 0);
-    p.merge_slots.clear();
+    p.slot_ids.clear();
     p.merge_cnt.assign(B, 0);
     p.merge_stride = 1;
     p.merge_kind.assign(B, kMergeDirect);
@@ -486,8 +484,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
             const size_t o_c1 = append(buf, p->chunks[1]);
             const size_t o_mem = append(buf, p->members);
             const size_t o_ids = append(buf, p->block_ids);
-            const size_t o_off = append(buf, p->merge_off);
-            const size_t o_slots = append(buf, p->merge_slots);
+            const size_t o_slots = append(buf, p->slot_ids);
             const size_t o_kind = append(buf, p->merge_kind);
             const size_t o_cnt = append(buf, p->merge_cnt);
             hipError_t e = hipGetDevice(&p->device);
@@ -507,8 +504,7 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
                 p->d.n_chunks[1] = (int32_t)p->chunks[1].size();
                 p->d.members = (const int32_t *)(d + o_mem);
                 p->d.block_ids = (const int32_t *)(d + o_ids);
-                p->d.merge_off = (const int32_t *)(d + o_off);
-                p->d.merge_slots = (const int32_t *)(d + o_slots);
+                p->d.slot_ids = (const int32_t *)(d + o_slots);
                 p->d.merge_kind = (const int32_t *)(d + o_kind);
                 p->d.merge_cnt = (const int32_t *)(d + o_cnt);
             }
