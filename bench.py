@@ -32,8 +32,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 def _parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
     ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3,mixed (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
