@@ -165,8 +165,10 @@ def bench_prefill(glm, w, steps, warmup):
     plan = glm.glm_plan_create(g, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
     mq = int(w.q_lens.max())
 
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+
     def step(i):
-        glm.glm_attn_prefill_on_prefix(g, pool, q, out, tables, w.max_blocks, lens, cu, w.B, w.sum_q, mq, w.scale, plan, None)
+        glm.glm_attn_prefill_on_prefix(g, pool, q, out, tables, w.max_blocks, lens, cu, w.B, w.sum_q, mq, w.scale, plan, ws)
 
     ms = _time_steps(step, steps, warmup)
     kt = _kernel_times(glm, step, min(steps, 16))
@@ -267,6 +269,42 @@ def bench_mixed(glm, w, steps, warmup):
 
         ms = _time_steps(step, steps, warmup)
         res[name] = {"ms_per_step": ms, "kernels": _kernel_times(glm, step, min(steps, 16)), "TFLOPs": w.flops() / ms / 1e9}
+    return res
+
+
+def bench_short_turn(glm, w, steps, warmup):
+    """Few new tokens on long cached contexts: the plan cuts the K/V ranges into chunks (partial results, merged per
+    new token); for comparison the same batch planned without that (GLM_PLAN_PREFILL_SPLIT=0 at plan time)."""
+    import torch
+    g = w.geom
+    pool, q, tables, lens, cu = _dev(w.pool), _dev(w.q), _dev(w.block_tables), _dev(w.seq_lens), _dev(w.cu_q_lens)
+    out = torch.empty((w.sum_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    mq = int(w.q_lens.max())
+    res = {"workload": w.name, "requests": int(w.B), "new_tokens": [int(x) for x in w.q_lens],
+           "seq_lens": [int(x) for x in w.seq_lens], "flops": w.flops(), "unique_kv_bytes": w.unique_kv_bytes()}
+    for name, flag in (("keys_cut_into_chunks", None), ("one_workgroup_per_row_tile", "0")):
+        old = os.environ.get("GLM_PLAN_PREFILL_SPLIT")
+        if flag is not None:
+            os.environ["GLM_PLAN_PREFILL_SPLIT"] = flag
+        try:
+            plan = glm.glm_plan_create(g, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+        finally:
+            if old is None:
+                os.environ.pop("GLM_PLAN_PREFILL_SPLIT", None)
+            else:
+                os.environ["GLM_PLAN_PREFILL_SPLIT"] = old
+        ws = torch.empty(max(16, plan.workspace_bytes), dtype=torch.uint8, device="cuda")
+
+        def step(i):
+            glm.glm_attn_prefill_on_prefix(g, pool, q, out, tables, w.max_blocks, lens, cu, w.B, w.sum_q, mq, w.scale, plan, ws)
+
+        ms = _time_steps(step, steps, warmup)
+        ent = [c for c in plan.chunks() if c.n_mem]
+        res[name] = {"ms_per_step": ms, "kernels": _kernel_times(glm, step, min(steps, 16)), "TFLOPs": w.flops() / ms / 1e9,
+                     "GBps_unique": (w.unique_kv_bytes() + w.q.nbytes + out.numel() * 4) / ms / 1e6,
+                     "workgroups": len(ent), "chunks_per_request": len({c.b0 for c in ent if c.rep == 0}),
+                     "workspace_bytes": int(plan.workspace_bytes)}
+    res["speedup_from_cutting_keys"] = res["one_workgroup_per_row_tile"]["ms_per_step"] / res["keys_cut_into_chunks"]["ms_per_step"]
     return res
 
 
@@ -389,7 +427,7 @@ def main():
         sys.exit(1)
     import paper_2511_01633_amd as glm
     import workloads as W
-    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3", "mixed"}
+    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3", "mixed", "short"}
     torch.cuda.set_device(0)
     extra = {}
 
@@ -403,6 +441,8 @@ def main():
             extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "mixed" in only:
             extra["mixed_batch"] = bench_mixed(glm, W.mixed_batch(), max(10, args.steps // 4), max(2, args.warmup // 4))
+        if "short" in only:
+            extra["short_turn_prefill"] = bench_short_turn(glm, W.short_turn_prefill(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "qwen3" in only:
             extra["qwen3_moe_decode"] = bench_decode(glm, W.qwen3_moe_decode(), args.layers, max(10, args.steps // 2),
                                                      max(2, args.warmup // 2))

@@ -100,11 +100,14 @@ GLM_API int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_d
  *   cu_q_lens_dev      int32 [B+1], cu_q_lens[0] = 0, cu_q_lens[B] = sum_q
  *   max_q_len          upper bound of q_len_r (sizes the launch when there is no plan)
  *   plan               NULL or a plan made with q_lens_host != NULL for these lengths
- *   workspace_dev      needed only with a plan of a mixed batch: requests with one new token (decode steps of
- *                      some agents among other agents' prefills, Sec. 6.1 serves them concurrently) are planned
- *                      as split-K items like a decode batch, their partial results live here;
- *                      glm_plan_workspace_bytes gives the size (0 if the batch has no such request), too small
- *                      -> GLM_ERR_WORKSPACE.  May be NULL otherwise.
+ *   workspace_dev      with a plan, at least glm_plan_workspace_bytes(plan) bytes, 16-byte aligned; too small
+ *                      -> GLM_ERR_WORKSPACE.  Two kinds of plan leave partial results there: that of a mixed
+ *                      batch (requests with one new token, decode steps of some agents among other agents'
+ *                      prefills, Sec. 6.1 serves them concurrently, are planned as split-K items like a decode
+ *                      batch) and that of a small batch on long contexts (fewer 128-row tiles than the chip has
+ *                      workgroup slots: the K/V range of each request is cut into chunks, one slot per
+ *                      (new token, chunk), merged per token).  Without a plan, or when the plan has no partial
+ *                      results, it is not read and may be NULL.
  * Errors as for glm_attn_decode; RANGE also covers q_len > seq_len and a cu_q_lens that does
  * not end at sum_q.  B == 0 or sum_q == 0 returns GLM_OK without a launch.
  */

@@ -371,44 +371,123 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
 // prefills; those rows are planned like a decode batch of their own (prefix tree over them, split-K items for
 // the wave-private launch, merge lists), the others as 128-row tiles of the cooperative launch.
 int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, const int32_t *q_lens) {
-    const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
+    const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads, Hkv = p.g.num_kv_heads;
     const int32_t tile_rows = kCoopRows;
     const bool mixed = env_int("GLM_PLAN_MIXED", 1) != 0 && G <= kRowsPerWave;
     std::vector<int32_t> one_token;
-    std::vector<Work> work;
+    std::vector<int64_t> cu(B + 1, 0);
+    int64_t wgs = 0;
     for (int32_t r = 0; r < B; ++r) {
         if (q_lens[r] < 0 || seq_lens[r] < q_lens[r] || ceil_div(seq_lens[r], kBlockSize) > p.max_blocks)
             return GLM_ERR_RANGE;
+        cu[r + 1] = cu[r] + q_lens[r];
         if (mixed && q_lens[r] == 1) { one_token.push_back(r); continue; }
+        wgs += (int64_t)ceil_div((int64_t)q_lens[r] * G, (int64_t)tile_rows) * Hkv;
+    }
+    // A small batch (few new tokens on long contexts: an agent's short turn on a cached notebook, Sec. 5.2)
+    // has fewer row tiles than the chip has workgroup slots, each walking a long run of keys.  Its K/V range
+    // is then cut into chunks (split-K): every (row tile, chunk) is a workgroup that leaves partial results,
+    // one slot per (new token, chunk), merged per token afterwards.  The number of chunks minimises an
+    // estimate of the call's time: the longest walk (microseconds per block measured for one and for two
+    // workgroups per compute unit; beyond 512 workgroups they queue) plus what the partial results cost
+    // (written once, read once by the merge, at about 3 TB/s, and the merge launch itself).
+    int32_t want_split = 1;
+    const int forced = env_int("GLM_PLAN_PREFILL_SPLIT", -1);      // 0: never; n > 1: n chunks, whatever the estimate
+    const int32_t min_chunk = std::max(2, env_int("GLM_PLAN_PREFILL_MIN_CHUNK_BLOCKS", 16));
+    if (one_token.empty() && wgs > 0 && forced != 0) {
+        int32_t nb_max = 0;
+        for (int32_t r = 0; r < B; ++r) nb_max = std::max(nb_max, ceil_div(seq_lens[r], kBlockSize));
+        const double width = p.g.head_dim == 64 ? 0.6 : 1.0;
+        const double slot_mb = (double)cu[B] * p.g.num_q_heads * (p.g.head_dim + 2) * 4e-6;
+        auto estimate = [&](int32_t ns) {
+            const double n_wg = (double)wgs * ns;
+            const double per_block = width * (n_wg <= 256 ? 0.27 : 0.45 * std::max(1.0, n_wg / 512.0));
+            return ceil_div(nb_max, ns) * per_block + (ns > 1 ? 6.0 + 2.0 * slot_mb * ns / 3.0 : 0.0);
+        };
+        double best = estimate(1) * 0.9;                            // a split has to promise a tenth at least
+        for (int32_t ns : {2, 3, 4, 6, 8, 12, 16, 24, 32}) {
+            if (ceil_div(nb_max, ns) < min_chunk) break;
+            const double t = estimate(ns);
+            if (t < best) { best = t; want_split = ns; }
+        }
+        if (forced > 1) want_split = std::min(forced, 32);
+    }
+    std::vector<int32_t> chunk_of(B, 0), nchunks_of(B, 1);
+    int32_t stride = 1;
+    for (int32_t r = 0; r < B; ++r) {
+        const int32_t nb = ceil_div(seq_lens[r], kBlockSize);
+        int32_t cb = std::max(min_chunk, ceil_div(nb, want_split));
+        cb = (cb + 1) & ~1;                                   // whole tiles of two blocks
+        chunk_of[r] = cb;
+        nchunks_of[r] = (want_split > 1 && q_lens[r] > 1) ? std::max(1, ceil_div(nb, cb)) : 1;
+        if (!(mixed && q_lens[r] == 1)) stride = std::max(stride, nchunks_of[r]);
+    }
+    const bool split = stride > 1;
+    p.slot_ids.clear();
+    std::vector<Work> work;
+    for (int32_t r = 0; r < B; ++r) {
+        if (mixed && q_lens[r] == 1) continue;
         const int64_t rows = (int64_t)q_lens[r] * G;
         const int64_t ctx = seq_lens[r] - q_lens[r];
-        for (int64_t row0 = 0; row0 < rows; row0 += tile_rows) {
-            glm_chunk c{};
-            c.rep = r;
-            c.b0 = 0;
-            c.b1 = INT32_MAX;
-            c.mem_off = 0;
-            c.n_mem = q_lens[r];
-            c.row0 = (int32_t)row0;
-            c.slot0 = -1;
-            c.waves = kBigWaves;
-            const int64_t last_pos = std::min<int64_t>(rows, row0 + tile_rows) - 1;
-            const int64_t visible = ctx + last_pos / G + 1;
-            for (int32_t kvh = 0; kvh < p.g.num_kv_heads; ++kvh) {
-                Work wk{};
-                wk.c[0] = c;
-                wk.c[0].kvh = kvh;
-                wk.n = 1;
-                wk.cost = ceil_div(visible, kBlockSize);
-                wk.bytes = row0 == 0 ? wk.cost : 0;
-                wk.group = r * p.g.num_kv_heads + kvh;      // the tiles of one (request, kv head) walk the same K/V
-                work.push_back(wk);
+        const int32_t nb = ceil_div(seq_lens[r], kBlockSize), cb = chunk_of[r], nch = nchunks_of[r];
+        for (int32_t k = 0; k < nch; ++k) {
+            const int32_t c0 = k * cb, c1 = (k == nch - 1) ? nb : (k + 1) * cb;
+            int32_t slot0 = -1;
+            if (nch > 1) {                                     // token mi of the request leaves its k-th partial here
+                slot0 = (int32_t)p.slot_ids.size();
+                for (int32_t mi = 0; mi < q_lens[r]; ++mi) p.slot_ids.push_back((int32_t)((cu[r] + mi) * stride + k));
+            }
+            for (int64_t row0 = 0; row0 < rows; row0 += tile_rows) {
+                const int64_t last_pos = std::min<int64_t>(rows, row0 + tile_rows) - 1;
+                const int64_t visible = ctx + last_pos / G + 1;           // keys the tile's last row sees
+                if ((int64_t)c0 * kBlockSize >= visible) continue;           // the chunk lies behind every row of the tile
+                glm_chunk c{};
+                c.rep = r;
+                c.b0 = c0;
+                c.b1 = (k == nch - 1) ? INT32_MAX : c1;
+                c.mem_off = 0;
+                c.n_mem = q_lens[r];
+                c.row0 = (int32_t)row0;
+                c.slot0 = slot0;
+                c.waves = kBigWaves;
+                const int64_t seen = std::min<int64_t>(ceil_div(visible, (int64_t)kBlockSize), c1) - c0;
+                for (int32_t kvh = 0; kvh < Hkv; ++kvh) {
+                    Work wk{};
+                    wk.c[0] = c;
+                    wk.c[0].kvh = kvh;
+                    wk.n = 1;
+                    wk.cost = seen;
+                    wk.bytes = row0 == 0 ? wk.cost : 0;
+                    wk.group = (r * stride + k) * Hkv + kvh;     // the tiles of one (request, chunk, kv head) walk the same K/V
+                    work.push_back(wk);
+                }
             }
         }
     }
     p.chunks[0].clear();
     p.chunks[1] = deal_to_xcds(work, 1);
     p.members.clear();
+    p.merge_stride = stride;
+    p.merge_by_token = false;
+    if (split) {
+        // one merge unit per new token: token t owns the slots t * stride .., its count is the number of chunks
+        // that start at or before its own position
+        const int64_t sum_q = cu[B];
+        p.merge_by_token = true;
+        p.n_slots = (int32_t)(sum_q * stride);
+        p.merge_cnt.assign((size_t)sum_q, 0);
+        p.merge_kind.assign((size_t)sum_q, kMergeDirect);
+        for (int32_t r = 0; r < B; ++r) {
+            if (nchunks_of[r] <= 1) continue;
+            const int64_t ctx = seq_lens[r] - q_lens[r];
+            for (int32_t mi = 0; mi < q_lens[r]; ++mi) {
+                const int64_t pos = ctx + mi;
+                p.merge_cnt[(size_t)(cu[r] + mi)] = (int32_t)std::min<int64_t>(nchunks_of[r], pos / ((int64_t)chunk_of[r] * kBlockSize) + 1);
+                p.merge_kind[(size_t)(cu[r] + mi)] = kMergeList;
+            }
+        }
+        return GLM_OK;
+    }
     p.slot_ids.clear();
     p.merge_cnt.assign(B, 0);
     p.merge_stride = 1;

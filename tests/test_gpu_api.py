@@ -17,6 +17,27 @@ def _gu():
     return gpu_util
 
 
+def test_split_prefill_plan_needs_its_workspace():
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    # a small batch on a long context is planned with partial results: the call then needs the plan's workspace
+    ws_w = W.custom_prefill(5002, prefix_groups=[[0]], prefix_tokens=[4096], q_lens=[64], num_q_heads=8, num_kv_heads=2,
+                            head_dim=128)
+    ds = gu.DeviceWorkload(ws_w)
+    sp = ds.make_plan()
+    assert sp.workspace_bytes > 256
+
+    def scall(ws, plan=sp, sum_q=ws_w.sum_q):
+        return glm.glm_attn_prefill_on_prefix(ws_w.geom, ds.pool, ds.q, ds.out, ds.tables, ws_w.max_blocks, ds.seq_lens,
+                                              ds.cu, ws_w.B, sum_q, 64, ws_w.scale, plan, ws, check=False)
+    assert scall(None) == glm.GLM_ERR_WORKSPACE
+    assert scall(torch.empty(sp.workspace_bytes - 16, dtype=torch.uint8, device="cuda")) == glm.GLM_ERR_WORKSPACE
+    good = torch.empty(sp.workspace_bytes, dtype=torch.uint8, device="cuda")
+    assert scall(good, sum_q=ws_w.sum_q - 1) == glm.GLM_ERR_PLAN_MISMATCH        # the plan merges per new token
+    assert scall(good) == glm.GLM_OK
+    torch.cuda.synchronize()
+
+
 @pytest.fixture
 def validate_env():
     old = os.environ.get("GLM_VALIDATE")

@@ -207,8 +207,8 @@ def _prefill_both_ways(w, what):
     if (w.q_lens == 1).any():
         # one-token requests take the split-K decode path under a plan: same result up to summation order
         assert np.abs(got_p - got).max() <= 1e-5
-    else:
-        np.testing.assert_array_equal(got_p, got)
+    elif not any(c.slot0 >= 0 for c in plan.chunks()):
+        np.testing.assert_array_equal(got_p, got)       # (a plan that cuts the keys into chunks merges partials)
     return got, ref
 
 
@@ -227,6 +227,34 @@ def test_prefill_fewer_or_more_requests_than_xcds(B, hq, hkv, d):
     w = W.custom_prefill(3200 + B, prefix_groups=[list(range(B))], prefix_tokens=[100], q_lens=q_lens, num_q_heads=hq,
                          num_kv_heads=hkv, head_dim=d)
     _prefill_both_ways(w, "prefill B=%d %d/%d d%d" % (B, hq, hkv, d))
+
+
+@pytest.mark.parametrize("d,forced", [(128, None), (64, None), (128, "3"), (64, "5"), (128, "32")])
+def test_prefill_small_batch_cuts_keys_into_chunks(d, forced):
+    """Few new tokens on long cached contexts: the plan cuts each request's K/V range into chunks, every (row tile,
+    chunk) leaves partial results and each new token merges those of the chunks that start at or before its own
+    position.  The new tokens of request 0 straddle chunk boundaries (causal limits inside a chunk, tokens that
+    see different numbers of chunks), request 1 is shorter than the others, request 2 has one row tile only."""
+    gu = _gu()
+    w = W.custom_prefill(3300 + d, prefix_groups=[[0, 2]], prefix_tokens=[1504], q_lens=[700, 90, 9],
+                         cached_suffix_tokens=[37, 300, 1000], num_q_heads=8, num_kv_heads=2, head_dim=d)
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan() if forced is None else _with_env("GLM_PLAN_PREFILL_SPLIT", forced, dw.make_plan)
+    chunks = [c for c in plan.chunks() if c.n_mem]
+    assert any(c.slot0 >= 0 and c.b0 > 0 for c in chunks), "the plan was expected to split"
+    if forced is not None:
+        nb = -(-int(w.seq_lens[0]) // 16)
+        cb = (max(16, -(-nb // int(forced))) + 1) // 2 * 2             # chunks are whole tiles, 16 blocks at least
+        assert len({c.b0 for c in chunks if c.rep == 0}) == -(-nb // cb)
+    assert plan.workspace_bytes >= 4 * (d + 2) * 8 * w.sum_q * 2
+    got = dw.prefill(plan=plan)
+    _check(got, ref, "prefill split-K d%d %s" % (d, forced))
+    # and the unsplit plan of the same batch agrees to rounding (the weights are rounded to bf16 against a
+    # different running maximum)
+    plain = _with_env("GLM_PLAN_PREFILL_SPLIT", "0", dw.make_plan)
+    assert not any(c.slot0 >= 0 for c in plain.chunks())
+    assert np.abs(dw.prefill(plan=plain) - got).max() <= 2e-3
 
 
 def test_prefill_without_any_cached_prefix_and_row_vs_decode():
@@ -270,6 +298,20 @@ def test_prefill_on_prefix_full_sampled():
     _check(got[rows, head], ref, "prefill_on_prefix (192 sampled rows)")
     got_np = dw.prefill(plan=None)
     np.testing.assert_array_equal(got_np, got)
+
+
+def test_short_turn_prefill_full():
+    """The benchmark's short turn on long cached contexts, in the launch configuration it is timed in (K/V ranges
+    cut into chunks, partial results merged per new token): every row against the oracle."""
+    gu = _gu()
+    w = W.short_turn_prefill()
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    assert any(c.slot0 >= 0 and c.b0 > 0 for c in plan.chunks())
+    got = dw.prefill(plan=plan)
+    ref = _oracle(w)
+    _check(got, ref, "short_turn_prefill (plan)")
+    _check(dw.prefill(plan=None), ref, "short_turn_prefill (no plan)")
 
 
 def test_tree_decode_70b_full_sampled():

@@ -146,6 +146,58 @@ def test_cooperative_work_is_spread_over_all_xcds():
     assert min(per_xcd) == max(per_xcd) == 1024 * 4 // 128, per_xcd          # one kv head's row tiles per XCD
 
 
+@pytest.mark.parametrize("forced", [None, "3", "32"])
+def test_small_prefill_plan_cuts_keys_into_chunks(forced, monkeypatch):
+    """A prefill batch with fewer row tiles than the chip has workgroup slots is planned with its K/V range cut into
+    chunks.  Every (new token, head, visible block) is covered by exactly one entry, entries of chunks that no row
+    of a tile can see are left out, and the workspace holds one slot per (new token, chunk)."""
+    if forced is not None:
+        monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", forced)
+    w = W.custom_prefill(11, prefix_groups=[[0, 1]], prefix_tokens=[2048], q_lens=[600, 40], cached_suffix_tokens=[0, 500],
+                         num_q_heads=8, num_kv_heads=2, head_dim=128)
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    G = w.geom.group
+    chunks = [c for c in plan.chunks() if c.n_mem]
+    assert all(c.waves == 4 for c in chunks)
+    starts = {r: sorted({c.b0 for c in chunks if c.rep == r}) for r in range(w.B)}
+    assert len(starts[0]) > 1, "the plan was expected to split"
+    if forced == "3":
+        assert len(starts[0]) == 3
+    seen = {}
+    for c in chunks:
+        r = c.rep
+        assert c.n_mem == w.q_lens[r] and c.b0 % 2 == 0
+        split = len(starts[r]) > 1
+        assert (c.slot0 >= 0) == split
+        ctx = int(w.seq_lens[r] - w.q_lens[r])
+        rows = range(c.row0, min(c.n_mem * G, c.row0 + 128))
+        assert c.b0 * 16 < ctx + rows[-1] // G + 1                  # some row of the tile sees the chunk
+        for rho in rows:
+            mi, gh = rho // G, rho % G
+            nb = -(-(ctx + mi + 1) // 16)                          # blocks visible to this new token
+            end = nb if c.b1 == 2 ** 31 - 1 else min(c.b1, nb)
+            for b in range(c.b0, end):
+                key = (r, mi, c.kvh * G + gh, b)
+                seen[key] = seen.get(key, 0) + 1
+    want = 0
+    for r in range(w.B):
+        ctx = int(w.seq_lens[r] - w.q_lens[r])
+        for mi in range(int(w.q_lens[r])):
+            want += -(-(ctx + mi + 1) // 16) * w.geom.num_q_heads
+    assert len(seen) == want and set(seen.values()) == {1}
+    stride = max(len(v) for v in starts.values())
+    assert plan.workspace_bytes == w.sum_q * stride * w.geom.num_q_heads * (128 + 2) * 4
+    monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", "0")
+    plain = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    assert all(c.slot0 < 0 and c.b0 == 0 for c in plain.chunks())
+    # a batch that fills the chip is never split
+    monkeypatch.delenv("GLM_PLAN_PREFILL_SPLIT")
+    wb = W.custom_prefill(12, prefix_groups=[list(range(8))], prefix_tokens=[2048], q_lens=[512] * 8, num_q_heads=32,
+                          num_kv_heads=8, head_dim=128)
+    big = glm.glm_plan_create_host(wb.geom, wb.block_tables, wb.max_blocks, wb.seq_lens, wb.q_lens, wb.B)
+    assert all(c.slot0 < 0 for c in big.chunks())
+
+
 def test_plan_handles_partial_sharing_and_unequal_lengths():
     # request 1 ends inside the run shared with request 0; request 2 shares only the first block
     tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)

@@ -23,6 +23,7 @@ from .gen import (  # noqa: F401
     llama8b_decode,
     qwen3_moe_decode,
     mixed_batch,
+    short_turn_prefill,
     prefill_on_prefix,
     tree_decode_70b,
     eviction_churn,

@@ -360,6 +360,20 @@ def prefill_on_prefix(seed: Optional[int] = None, *, branches: int = 16, prefix_
                           name="prefill_on_prefix")
 
 
+def short_turn_prefill(seed: Optional[int] = None, *, branches: int = 2, prefix_tokens: int = 4096,
+                       cached_lo: int = 1024, cached_hi: int = 3072, q_lo: int = 64, q_hi: int = 192) -> Workload:
+    """A short turn on a long cached context: few branches, each appending U{q_lo..q_hi} new tokens (a retrieved
+    node's text, a tool result) after the shared graph-context prefix and U{cached_lo..cached_hi} cached tokens
+    of its own (the agent's notebook so far, Sec. 5.2).  Llama-3-8B attention shape."""
+    seed = config_seed(7) if seed is None else seed
+    r2 = _rng(seed ^ 0x7A11)
+    q_lens = [int(r2.integers(q_lo, q_hi + 1)) for _ in range(branches)]
+    sfx = [int(r2.integers(cached_lo, cached_hi + 1)) for _ in range(branches)]
+    return custom_prefill(seed, prefix_groups=[list(range(branches))], prefix_tokens=[prefix_tokens], q_lens=q_lens,
+                          cached_suffix_tokens=sfx, num_q_heads=32, num_kv_heads=8, head_dim=128,
+                          name="short_turn_prefill")
+
+
 def tree_decode_70b(seed: Optional[int] = None, *, root_tokens: int = 8192, mids: int = 8, mid_tokens: int = 1024,
                     leaves_per_mid: int = 32, suffix_tokens: int = 256, num_q_heads: int = 64,
                     num_kv_heads: int = 8, head_dim: int = 128, block_size: int = 16) -> Workload:
