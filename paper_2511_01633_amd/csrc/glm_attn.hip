@@ -860,10 +860,13 @@ __global__ void __launch_bounds__(256, 2) attn_fused_kernel(const AttnArgs a) {
 
 // Combines a request's partial results in list order:
 //   M = max m_i,  l = sum l_i 2^(m_i-M),  out = sum acc_i 2^(m_i-M) / l.
-template <int D>
-__global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
+// One workgroup of NW waves per (request, head).  With NW = 4 (long lists: a lone wave needs about 0.1 us
+// per partial, its fetches are dependent round trips) wave w combines the w-th quarter of the list and
+// wave 0 combines the four results in wave order, so the order of accumulation stays fixed.
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW) attn_merge_kernel(const MergeArgs a) {
     const int r = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int E = D / 64;
     const int64_t out_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
     float *dst = a.out + (out_row * a.Hq + h) * D + lane * E;
@@ -884,7 +887,7 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
     };
     float my_m = -INFINITY, my_l = 0.f;
     float v[8][E];
-    if (a.have_partials) {          // (without partial slots there is no workspace to read, and nothing to merge)
+    if (NW == 1 && a.have_partials) {   // (without partial slots there is no workspace to read, and nothing to merge)
         if (lane < stride) {
             my_m = a.part_ml[(row0 + (int64_t)lane * a.Hq) * 2];
             my_l = a.part_ml[(row0 + (int64_t)lane * a.Hq) * 2 + 1];
@@ -897,22 +900,27 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
         n = min(a.merge_cnt[r], stride);
         if (kind == kMergeDirect) return;
         if (kind == kMergeZero) {
+            if (wave == 0) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) dst[e] = 0.f;
+                for (int e = 0; e < E; ++e) dst[e] = 0.f;
+            }
             return;
         }
     } else {
         const int nb = min((a.seq_lens[r] + kBlockSize - 1) / kBlockSize, a.max_blocks);
         n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
     }
+    // this wave's part of the list
+    const int per = NW == 1 ? n : (((n + NW - 1) / NW + 7) & ~7);
+    const int lo = NW == 1 ? 0 : min(wave * per, n), hi = NW == 1 ? n : min(lo + per, n);
     float M = -INFINITY, l = 0.f, o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
     // 64 partials at a time: lane i holds (m, l) of partial i.  The running maximum M carries over between
     // groups and the order of accumulation is fixed.
-    for (int base = 0; base < n; base += 64) {
-        const int cnt = min(64, n - base);
-        if (base > 0) {
+    for (int base = lo; base < hi; base += 64) {
+        const int cnt = min(64, hi - base);
+        if (NW > 1 || base > 0) {
             my_m = -INFINITY; my_l = 0.f;
             if (lane < cnt) {
                 my_m = a.part_ml[(row0 + (int64_t)(base + lane) * a.Hq) * 2];
@@ -921,6 +929,7 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
         } else if (lane >= cnt) {
             my_m = -INFINITY; my_l = 0.f;
         }
+        if (NW > 1) fetch(base, base + cnt, v);
         float gm = my_m;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off));
@@ -937,13 +946,34 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(const MergeArgs a) {
         for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
         l += lw;
         for (int i0 = 0; i0 < cnt; i0 += 8) {               // 8 independent fetches in flight at a time
-            if (base > 0 || i0 > 0) fetch(base + i0, base + cnt, v);
+            if (i0 > 0 || (NW == 1 && base > 0)) fetch(base + i0, base + cnt, v);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float w = (i0 + j < cnt) ? __shfl(my_w, min(i0 + j, cnt - 1)) : 0.f;
 #pragma unroll
                 for (int e = 0; e < E; ++e) o[e] += (i0 + j < cnt) ? v[j][e] * w : 0.f;
             }
+        }
+    }
+    if (NW > 1) {
+        __shared__ float w_M[NW], w_l[NW], w_o[NW][D];
+        if (lane == 0) { w_M[wave] = M; w_l[wave] = l; }
+#pragma unroll
+        for (int e = 0; e < E; ++e) w_o[wave][lane * E + e] = o[e];
+        __syncthreads();
+        if (wave != 0) return;
+        float Mt = w_M[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) Mt = fmaxf(Mt, w_M[w]);
+        l = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = (w_M[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w_M[w] - Mt);
+            l += w_l[w] * f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] += w_o[w][lane * E + e] * f;
         }
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
@@ -1008,11 +1038,23 @@ hipError_t launch_fused(int D, AttnArgs &a, int64_t n_coop, int64_t n_priv, hipS
     return hipGetLastError();
 }
 
+int merge_wide_from() {
+    const char *s = std::getenv("GLM_MERGE_WIDE_FROM");
+    return s && *s ? std::atoi(s) : 16;
+}
+
 hipError_t launch_merge(int D, const MergeArgs &m, int grid, hipStream_t st) {
     if (grid <= 0) return hipSuccess;
     ProfileScope prof(kKernelMerge, st);
-    if (D == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(grid), dim3(64), 0, st, m);
-    else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(grid), dim3(64), 0, st, m);
+    // lists of more than 16 partials are combined by four waves
+    const int stride = m.merge_kind ? m.merge_stride : m.n_split;
+    if (stride > merge_wide_from()) {
+        if (D == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 4>), dim3(grid), dim3(256), 0, st, m);
+        else hipLaunchKernelGGL((attn_merge_kernel<64, 4>), dim3(grid), dim3(256), 0, st, m);
+    } else {
+        if (D == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 1>), dim3(grid), dim3(64), 0, st, m);
+        else hipLaunchKernelGGL((attn_merge_kernel<64, 1>), dim3(grid), dim3(64), 0, st, m);
+    }
     return hipGetLastError();
 }
 

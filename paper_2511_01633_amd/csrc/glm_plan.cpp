@@ -214,8 +214,15 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
 
     // Segments with many rows go to the cooperative kernel (64 rows per workgroup share one staged
     // K/V tile); the rest is cut into wave-private items of 16 rows.
+    // A cooperative workgroup spends about 7 us outside its tile loop, so a short run that fills a single
+    // row tile is served sooner by wave-private items that re-read it through L2 (measured on 128-row runs:
+    // 128 blocks are faster wave-private, 512 blocks faster cooperative); from two row tiles on the
+    // cooperative kernel wins or draws at every length measured.
     const int coop_min_rows = env_int("GLM_PLAN_COOP_MIN_ROWS", 128);
-    auto is_coop = [&](int64_t rows) { return !subset && rows >= coop_min_rows; };
+    const int64_t coop_min_work = env_int("GLM_PLAN_COOP_MIN_ROW_BLOCKS", 32768);
+    auto is_coop = [&](int64_t rows, int64_t blocks) {
+        return !subset && rows >= coop_min_rows && (rows >= 2 * kCoopRows || rows * blocks >= coop_min_work);
+    };
     // Chunk length, separately for the two launches.  Wave-private items: a little fewer items than the
     // chip has wave slots (2 per SIMD = 2048), so that the launch, padding included, is one round; at
     // least 4 tiles each.
@@ -225,7 +232,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     int64_t units_coop = 0;
     for (auto &s : segs) {
         const int64_t rows = (int64_t)s.members.size() * G;
-        if (is_coop(rows)) units_coop += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kCoopRows);
+        if (is_coop(rows, s.b1 - s.b0)) units_coop += (int64_t)(s.b1 - s.b0) * ceil_div(rows, kCoopRows);
     }
     // Wave-private items all start together when the launch fits the chip's wave slots, and the launch
     // ends with its slowest wave.  Per-wave timelines on MI355X (64 branches on 4 prefixes, d = 128)
@@ -234,13 +241,20 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     // 1.16 (n + 3) when it streams alone.  Both chunk lengths are derived from one duration: the
     // shortest for which the launch still is one round.
     const int min_cb = env_int("GLM_PLAN_MIN_CHUNK_BLOCKS", 8), max_cb = env_int("GLM_PLAN_MAX_CHUNK_BLOCKS", 128);
-    const int target = env_int("GLM_PLAN_TARGET_ITEMS", 2040);
+    // A launch with little to stream is not bandwidth bound: one wave per SIMD walks its tiles faster than
+    // two do, so half the wave slots with items twice as long end sooner and leave half the partials
+    // (measured on 16 batches of 25 - 205 MB: below about 128 MB 1020 items win by 5 - 20 %, above 2040 do).
+    int64_t private_bytes = 0;
+    for (auto &s : segs)
+        if (!is_coop((int64_t)s.members.size() * G, s.b1 - s.b0))
+            private_bytes += (int64_t)(s.b1 - s.b0) * 2 * p.g.num_kv_heads * kBlockSize * p.g.head_dim * 2;
+    const int target = env_int("GLM_PLAN_TARGET_ITEMS", private_bytes < env_int("GLM_PLAN_SMALL_LAUNCH_MB", 128) * (int64_t)1000000 ? 1020 : 2040);
     auto clamp_cb = [&](int tiles) { return std::min(std::max(2 * tiles, min_cb), max_cb); };
     auto count_items = [&](int32_t cb_fam, int32_t cb_one) {
         int64_t n = 0;
         for (auto &s : segs) {
             const int64_t rows = (int64_t)s.members.size() * G;
-            if (is_coop(rows)) continue;
+            if (is_coop(rows, s.b1 - s.b0)) continue;
             n += (int64_t)ceil_div(s.b1 - s.b0, rows > kRowsPerWave ? cb_fam : cb_one) * ceil_div(rows, kRowsPerWave);
         }
         return n * p.g.num_kv_heads;
@@ -260,7 +274,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     int32_t cb_coop = (int32_t)std::max<int64_t>(env_int("GLM_PLAN_COOP_MIN_CHUNK_BLOCKS", 32), units_coop * p.g.num_kv_heads / std::max(1, target_coop));
     cb_coop = (cb_coop + 1) & ~1;
     if (int forced = env_int("GLM_PLAN_COOP_CHUNK_BLOCKS", 0)) cb_coop = std::max(1, forced);
-    auto chunk_blocks = [&](int64_t rows) { return is_coop(rows) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };
+    auto chunk_blocks = [&](int64_t rows, int64_t blocks) { return is_coop(rows, blocks) ? cb_coop : rows > kRowsPerWave ? cb_family : cb_single; };
 
     std::vector<int32_t> n_partials(B, 0);      // partial results of each request so far
     std::vector<Work> coop;
@@ -275,7 +289,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     std::vector<int32_t> n_chunks_of(B, 0);
     for (auto &s : segs) {
         const int32_t len = s.b1 - s.b0;
-        const int32_t nc = ceil_div(len, chunk_blocks((int64_t)s.members.size() * G));
+        const int32_t nc = ceil_div(len, chunk_blocks((int64_t)s.members.size() * G, len));
         for (int32_t r : s.members) n_chunks_of[r] += nc;
     }
     // A request's partial results get the slots r * stride + 0, 1, .. in the order its chunks are made (the merge
@@ -289,11 +303,11 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
         const int32_t mem_off = (int32_t)p.members.size();
         p.members.insert(p.members.end(), s.members.begin(), s.members.end());
         const int64_t rows = (int64_t)nm * G;
-        const bool cooperative = is_coop(rows);
+        const bool cooperative = is_coop(rows, s.b1 - s.b0);
         const int waves = cooperative ? kBigWaves : 1;
         const int32_t tile_rows = cooperative ? kCoopRows : kRowsPerWave;
         const int32_t len = s.b1 - s.b0;
-        const int32_t nc = ceil_div(len, chunk_blocks(rows));
+        const int32_t nc = ceil_div(len, chunk_blocks(rows, len));
         // spread the blocks evenly over the nc chunks, in whole tiles of 2 blocks
         int32_t per_chunk = ceil_div(len, nc);
         per_chunk = (per_chunk + 1) & ~1;

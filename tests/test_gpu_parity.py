@@ -493,8 +493,11 @@ def test_decode_wide_sharing_long_prefix_d64():
     """A decode run shared by 160 rows (cooperative launch) at d = 64 with a prefix longer than 64 blocks."""
     w = W.custom_decode(9300, prefix_groups=[list(range(40))], prefix_tokens=[1200], suffix_tokens=[int(x) for x in range(3, 43)],
                         num_q_heads=8, num_kv_heads=2, head_dim=64)
-    # with a plan the shared run goes to the cooperative launch, whose weights are plain bf16 beyond 1024 keys
-    _decode_both_ways(w, "decode 160 shared rows d=64", agree=5e-4)
+    # with a plan the shared run goes to the cooperative launch (forced: a run this short would be planned as
+    # wave-private items), whose weights are plain bf16 beyond 1024 keys
+    _, plan, _, _ = _with_env("GLM_PLAN_COOP_MIN_ROW_BLOCKS", "0",
+                              lambda: _decode_both_ways(w, "decode 160 shared rows d=64", agree=5e-4))
+    assert any(c.waves == 4 and c.n_mem for c in plan.chunks())
 
 
 def _with_env(name, value, fn):
@@ -517,7 +520,7 @@ def test_fused_launch_equals_separate_launches(d):
     w = W.custom_decode(9400 + d, prefix_groups=[list(range(40))], prefix_tokens=[700], suffix_tokens=[int(x) for x in range(3, 43)],
                         num_q_heads=8, num_kv_heads=2, head_dim=d)
     dw = gu.DeviceWorkload(w)
-    plan = dw.make_plan()
+    plan = _with_env("GLM_PLAN_COOP_MIN_ROW_BLOCKS", "0", dw.make_plan)     # (a run this short is wave-private otherwise)
     kinds = {c.waves for c in plan.chunks() if c.n_mem > 0}
     assert kinds == {1, 4}
     fused = _with_env("GLM_FUSED", "1", lambda: dw.decode(plan=plan))
