@@ -500,6 +500,26 @@ def test_decode_wide_sharing_long_prefix_d64():
     assert any(c.waves == 4 and c.n_mem for c in plan.chunks())
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_decode_long_merge_lists(d):
+    """Requests cut into many chunks (here 2 blocks each, forced): lists of more than 16 partials are combined by
+    four waves per (request, head), each a part of the list.  157, 10 and 66 partials: parts of 40, 8 and 24, so
+    some waves get a ragged part and some none."""
+    gu = _gu()
+    w = W.custom_decode(9500 + d, prefix_groups=[], prefix_tokens=[], suffix_tokens=[5000, 300, 2100], num_q_heads=8,
+                        num_kv_heads=2, head_dim=d)
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    plan = _with_env("GLM_PLAN_CHUNK_BLOCKS", "2", dw.make_plan)
+    per_req = [sum(1 for c in plan.chunks() if c.n_mem and c.rep == r) for r in range(3)]
+    assert per_req == [157, 10, 66]
+    got = dw.decode(plan=plan)
+    _check(got, ref, "decode, long merge lists d=%d" % d)
+    narrow = _with_env("GLM_MERGE_WIDE_FROM", "1000000", lambda: dw.decode(plan=plan))     # one wave per list
+    _check(narrow, ref, "decode, long merge lists, one merging wave d=%d" % d)
+    assert np.abs(narrow - got).max() <= 1e-5
+
+
 def _with_env(name, value, fn):
     old = os.environ.get(name)
     os.environ[name] = value
