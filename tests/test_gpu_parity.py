@@ -257,6 +257,28 @@ def test_prefill_small_batch_cuts_keys_into_chunks(d, forced):
     assert np.abs(dw.prefill(plan=plain) - got).max() <= 2e-3
 
 
+@pytest.mark.parametrize("case", range(4))
+def test_prefill_cut_keys_other_shapes(case):
+    """Chunked prefill plans on a lone request without a shared prefix, on requests without new tokens or with fewer
+    rows than a tile, and on contexts shorter than one chunk beside long ones (split count forced on the odd cases)."""
+    shapes = [
+        dict(prefix_groups=[], prefix_tokens=[], q_lens=[33], cached_suffix_tokens=[5000], num_q_heads=4, num_kv_heads=1, head_dim=64),
+        dict(prefix_groups=[[0, 1, 3]], prefix_tokens=[1024], q_lens=[300, 3, 0, 17], cached_suffix_tokens=[900, 0, 40, 2500],
+             num_q_heads=6, num_kv_heads=2, head_dim=128),
+        dict(prefix_groups=[[0, 1]], prefix_tokens=[4000], q_lens=[2, 70], cached_suffix_tokens=[13, 1], num_q_heads=16,
+             num_kv_heads=2, head_dim=64),
+        dict(prefix_groups=[[1, 2]], prefix_tokens=[512], q_lens=[64, 64, 64], cached_suffix_tokens=[0, 3000, 10],
+             num_q_heads=8, num_kv_heads=8, head_dim=128),
+    ]
+    gu = _gu()
+    w = W.custom_prefill(20 + case, **shapes[case])
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    plan = _with_env("GLM_PLAN_PREFILL_SPLIT", "7", dw.make_plan) if case % 2 else dw.make_plan()
+    assert any(c.slot0 >= 0 and c.b0 > 0 for c in plan.chunks())
+    _check(dw.prefill(plan=plan), ref, "chunked prefill, shape %d" % case)
+
+
 def test_prefill_without_any_cached_prefix_and_row_vs_decode():
     w = W.custom_prefill(3100, prefix_groups=[], prefix_tokens=[], q_lens=[4, 1, 37], num_q_heads=8, num_kv_heads=2,
                          head_dim=128)

@@ -146,29 +146,18 @@ def test_cooperative_work_is_spread_over_all_xcds():
     assert min(per_xcd) == max(per_xcd) == 1024 * 4 // 128, per_xcd          # one kv head's row tiles per XCD
 
 
-@pytest.mark.parametrize("forced", [None, "3", "32"])
-def test_small_prefill_plan_cuts_keys_into_chunks(forced, monkeypatch):
-    """A prefill batch with fewer row tiles than the chip has workgroup slots is planned with its K/V range cut into
-    chunks.  Every (new token, head, visible block) is covered by exactly one entry, entries of chunks that no row
-    of a tile can see are left out, and the workspace holds one slot per (new token, chunk)."""
-    if forced is not None:
-        monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", forced)
-    w = W.custom_prefill(11, prefix_groups=[[0, 1]], prefix_tokens=[2048], q_lens=[600, 40], cached_suffix_tokens=[0, 500],
-                         num_q_heads=8, num_kv_heads=2, head_dim=128)
-    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+def _prefill_cover(w, plan):
+    """Every (new token, head, visible block) is covered by exactly one entry of a prefill plan; returns the chunk
+    starts per request."""
     G = w.geom.group
     chunks = [c for c in plan.chunks() if c.n_mem]
     assert all(c.waves == 4 for c in chunks)
     starts = {r: sorted({c.b0 for c in chunks if c.rep == r}) for r in range(w.B)}
-    assert len(starts[0]) > 1, "the plan was expected to split"
-    if forced == "3":
-        assert len(starts[0]) == 3
     seen = {}
     for c in chunks:
         r = c.rep
         assert c.n_mem == w.q_lens[r] and c.b0 % 2 == 0
-        split = len(starts[r]) > 1
-        assert (c.slot0 >= 0) == split
+        assert (c.slot0 >= 0) == (len(starts[r]) > 1)
         ctx = int(w.seq_lens[r] - w.q_lens[r])
         rows = range(c.row0, min(c.n_mem * G, c.row0 + 128))
         assert c.b0 * 16 < ctx + rows[-1] // G + 1                  # some row of the tile sees the chunk
@@ -184,7 +173,24 @@ def test_small_prefill_plan_cuts_keys_into_chunks(forced, monkeypatch):
         ctx = int(w.seq_lens[r] - w.q_lens[r])
         for mi in range(int(w.q_lens[r])):
             want += -(-(ctx + mi + 1) // 16) * w.geom.num_q_heads
-    assert len(seen) == want and set(seen.values()) == {1}
+    assert len(seen) == want and set(seen.values()) <= {1}
+    return starts
+
+
+@pytest.mark.parametrize("forced", [None, "3", "32"])
+def test_small_prefill_plan_cuts_keys_into_chunks(forced, monkeypatch):
+    """A prefill batch with fewer row tiles than the chip has workgroup slots is planned with its K/V range cut into
+    chunks.  Every (new token, head, visible block) is covered by exactly one entry, entries of chunks that no row
+    of a tile can see are left out, and the workspace holds one slot per (new token, chunk)."""
+    if forced is not None:
+        monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", forced)
+    w = W.custom_prefill(11, prefix_groups=[[0, 1]], prefix_tokens=[2048], q_lens=[600, 40], cached_suffix_tokens=[0, 500],
+                         num_q_heads=8, num_kv_heads=2, head_dim=128)
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    starts = _prefill_cover(w, plan)
+    assert len(starts[0]) > 1, "the plan was expected to split"
+    if forced == "3":
+        assert len(starts[0]) == 3
     stride = max(len(v) for v in starts.values())
     assert plan.workspace_bytes == w.sum_q * stride * w.geom.num_q_heads * (128 + 2) * 4
     monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", "0")
@@ -196,6 +202,27 @@ def test_small_prefill_plan_cuts_keys_into_chunks(forced, monkeypatch):
                           num_kv_heads=8, head_dim=128)
     big = glm.glm_plan_create_host(wb.geom, wb.block_tables, wb.max_blocks, wb.seq_lens, wb.q_lens, wb.B)
     assert all(c.slot0 < 0 for c in big.chunks())
+
+
+@pytest.mark.parametrize("case", range(4))
+def test_small_prefill_plans_cover_every_token_once(case, monkeypatch):
+    """The same coverage property on other shapes: a lone request with no shared prefix, requests without new tokens
+    or with fewer tokens than a tile, contexts shorter than one chunk beside long ones, both head sizes."""
+    shapes = [
+        dict(prefix_groups=[], prefix_tokens=[], q_lens=[33], cached_suffix_tokens=[5000], num_q_heads=4, num_kv_heads=1, head_dim=64),
+        dict(prefix_groups=[[0, 1, 3]], prefix_tokens=[1024], q_lens=[300, 3, 0, 17], cached_suffix_tokens=[900, 0, 40, 2500],
+             num_q_heads=6, num_kv_heads=2, head_dim=128),
+        dict(prefix_groups=[[0, 1]], prefix_tokens=[4000], q_lens=[2, 70], cached_suffix_tokens=[13, 1], num_q_heads=16,
+             num_kv_heads=2, head_dim=64),
+        dict(prefix_groups=[[1, 2]], prefix_tokens=[512], q_lens=[64, 64, 64], cached_suffix_tokens=[0, 3000, 10],
+             num_q_heads=8, num_kv_heads=8, head_dim=128),
+    ]
+    if case % 2:
+        monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", "7")
+    w = W.custom_prefill(20 + case, **shapes[case])
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    starts = _prefill_cover(w, plan)
+    assert max(len(v) for v in starts.values()) > 1, "the plan was expected to split"
 
 
 def test_plan_handles_partial_sharing_and_unequal_lengths():
