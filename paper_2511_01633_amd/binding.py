@@ -23,7 +23,7 @@ GLM_ERR_PLAN_MISMATCH, GLM_ERR_RANGE, GLM_ERR_HIP, GLM_ERR_ALLOC = -5, -6, -7, -
 
 EXPORTS = (
     "glm_attn_decode", "glm_attn_prefill_on_prefix", "glm_kv_fork_copy", "glm_kv_gather", "glm_kv_append", "glm_kv_gather_tokens",
-    "glm_plan_create", "glm_plan_create_host", "glm_plan_destroy", "glm_plan_workspace_bytes",
+    "glm_plan_create", "glm_plan_create_host", "glm_plan_rebuild", "glm_plan_destroy", "glm_plan_workspace_bytes",
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
@@ -97,6 +97,8 @@ def _load() -> ctypes.CDLL:
     lib.glm_plan_create.restype = vp
     lib.glm_plan_create_host.argtypes = [glm_geom, vp, i32, vp, vp, i32, ctypes.POINTER(ctypes.c_int)]
     lib.glm_plan_create_host.restype = vp
+    lib.glm_plan_rebuild.argtypes = [vp, glm_geom, vp, i32, vp, vp, i32, vp]
+    lib.glm_plan_rebuild.restype = ctypes.c_int
     lib.glm_plan_destroy.argtypes = [vp]
     lib.glm_plan_destroy.restype = None
     lib.glm_plan_workspace_bytes.argtypes = [vp]
@@ -227,6 +229,15 @@ def glm_plan_create(g, block_tables_host, max_blocks: int, seq_lens_host, q_lens
     if not h:
         raise GlmError(st.value, "glm_plan_create")
     return Plan(h)
+
+
+def glm_plan_rebuild(plan: Plan, g, block_tables_host, max_blocks: int, seq_lens_host, q_lens_host, B: int, hip_stream=None,
+                     check: bool = True) -> int:
+    bt, sl, ql = _host_i32(block_tables_host), _host_i32(seq_lens_host), _host_i32(q_lens_host)
+    st = _lib.glm_plan_rebuild(plan.handle, geom(g), _hp(bt), max_blocks, _hp(sl), _hp(ql), B, _stream(hip_stream))
+    if check:
+        _check(st, "glm_plan_rebuild")
+    return st
 
 
 def glm_plan_create_host(g, block_tables_host, max_blocks: int, seq_lens_host, q_lens_host, B: int) -> Plan:

@@ -65,7 +65,10 @@ struct glm_plan {
     int32_t n_shared_segments = 0;
     int64_t shared_blocks = 0;
     void *dev = nullptr;              // device allocation, nullptr for host-only plans
+    size_t dev_capacity = 0;
     int device = -1;
     glm::DevicePlan d;
-    std::vector<char> staging;        // host image of the device allocation (kept for the async upload)
+    char *staging = nullptr;          // pinned host image of the device allocation (source of the async upload)
+    size_t staging_capacity = 0;
+    hipEvent_t uploaded = nullptr;    // recorded behind the last upload: the image may be rewritten once it has passed
 };

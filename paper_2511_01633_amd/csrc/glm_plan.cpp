@@ -511,12 +511,71 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
     return GLM_OK;
 }
 
-template <class T>
-size_t append(std::vector<char> &buf, const std::vector<T> &v) {
-    size_t off = (buf.size() + 255) & ~(size_t)255;
-    buf.resize(off + std::max<size_t>(v.size() * sizeof(T), sizeof(T)), 0);
-    if (!v.empty()) std::memcpy(buf.data() + off, v.data(), v.size() * sizeof(T));
-    return off;
+// Lays the plan's lists out in one image (256-byte aligned parts), in the plan's pinned host buffer, and copies
+// it to the plan's device buffer on `st`.  Both buffers are reused when they are large enough; a larger device
+// buffer replaces the old one only after the device has finished with it.
+struct ImagePart { const void *src; size_t bytes; size_t off; };
+
+int upload_plan(glm_plan *p, hipStream_t st) {
+    ImagePart parts[7] = {
+        {p->chunks[0].data(), p->chunks[0].size() * sizeof(glm_chunk), 0}, {p->chunks[1].data(), p->chunks[1].size() * sizeof(glm_chunk), 0},
+        {p->members.data(), p->members.size() * 4, 0}, {p->block_ids.data(), p->block_ids.size() * 4, 0},
+        {p->slot_ids.data(), p->slot_ids.size() * 4, 0}, {p->merge_kind.data(), p->merge_kind.size() * 4, 0},
+        {p->merge_cnt.data(), p->merge_cnt.size() * 4, 0}};
+    size_t total = 0;
+    for (ImagePart &q : parts) { q.off = total; total += (std::max<size_t>(q.bytes, 4) + 255) & ~(size_t)255; }
+    hipError_t e = hipSuccess;
+    if (!p->uploaded) e = hipEventCreateWithFlags(&p->uploaded, hipEventDisableTiming);
+    else e = hipEventSynchronize(p->uploaded);                  // the previous image has left the host buffer
+    if (e == hipSuccess && total > p->staging_capacity) {
+        if (p->staging) (void)hipHostFree(p->staging);
+        p->staging = nullptr;
+        p->staging_capacity = 0;
+        const size_t cap = total + total / 2;
+        e = hipHostMalloc((void **)&p->staging, cap, hipHostMallocDefault);
+        if (e == hipSuccess) p->staging_capacity = cap;
+    }
+    if (e == hipSuccess && total > p->dev_capacity) {
+        if (p->dev) {
+            // launches that read the old buffer may still be queued
+            e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = hipFree(p->dev);
+            p->dev = nullptr;
+            p->dev_capacity = 0;
+        }
+        const size_t cap = total + total / 2;
+        if (e == hipSuccess) e = hipMalloc(&p->dev, cap);
+        if (e == hipSuccess) p->dev_capacity = cap;
+    }
+    if (e != hipSuccess) return set_hip_error(e);
+    for (const ImagePart &q : parts)
+        if (q.bytes) std::memcpy(p->staging + q.off, q.src, q.bytes);
+    e = hipMemcpyAsync(p->dev, p->staging, total, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipEventRecord(p->uploaded, st);
+    if (e != hipSuccess) return set_hip_error(e);
+    const char *d = (const char *)p->dev;
+    p->d.chunks[0] = (const glm_chunk *)(d + parts[0].off);
+    p->d.chunks[1] = (const glm_chunk *)(d + parts[1].off);
+    p->d.n_chunks[0] = (int32_t)p->chunks[0].size();
+    p->d.n_chunks[1] = (int32_t)p->chunks[1].size();
+    p->d.members = (const int32_t *)(d + parts[2].off);
+    p->d.block_ids = (const int32_t *)(d + parts[3].off);
+    p->d.slot_ids = (const int32_t *)(d + parts[4].off);
+    p->d.merge_kind = (const int32_t *)(d + parts[5].off);
+    p->d.merge_cnt = (const int32_t *)(d + parts[6].off);
+    return GLM_OK;
+}
+
+void release_plan_buffers(glm_plan *p) {
+    if (p->dev) {
+        // launches that read the buffer, or its upload, may still be in flight
+        (void)hipDeviceSynchronize();
+        (void)hipFree(p->dev);
+    }
+    if (p->staging) (void)hipHostFree(p->staging);
+    if (p->uploaded) (void)hipEventDestroy(p->uploaded);
+    p->dev = nullptr; p->staging = nullptr; p->uploaded = nullptr;
+    p->dev_capacity = p->staging_capacity = 0;
 }
 
 }  // namespace
@@ -571,38 +630,10 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
     int st = GLM_OK;
     glm_plan *p = plan_build(g, block_tables_host, max_blocks, seq_lens_host, q_lens_host, B, &st);
     if (p) {
-        try {
-            std::vector<char> &buf = p->staging;
-            const size_t o_c0 = append(buf, p->chunks[0]);
-            const size_t o_c1 = append(buf, p->chunks[1]);
-            const size_t o_mem = append(buf, p->members);
-            const size_t o_ids = append(buf, p->block_ids);
-            const size_t o_slots = append(buf, p->slot_ids);
-            const size_t o_kind = append(buf, p->merge_kind);
-            const size_t o_cnt = append(buf, p->merge_cnt);
-            hipError_t e = hipGetDevice(&p->device);
-            if (e == hipSuccess) e = hipMalloc(&p->dev, buf.size());
-            if (e == hipSuccess)
-                e = hipMemcpyAsync(p->dev, buf.data(), buf.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
-            if (e != hipSuccess) {
-                st = set_hip_error(e);
-                if (p->dev) (void)hipFree(p->dev);
-                delete p;
-                p = nullptr;
-            } else {
-                char *d = (char *)p->dev;
-                p->d.chunks[0] = (const glm_chunk *)(d + o_c0);
-                p->d.chunks[1] = (const glm_chunk *)(d + o_c1);
-                p->d.n_chunks[0] = (int32_t)p->chunks[0].size();
-                p->d.n_chunks[1] = (int32_t)p->chunks[1].size();
-                p->d.members = (const int32_t *)(d + o_mem);
-                p->d.block_ids = (const int32_t *)(d + o_ids);
-                p->d.slot_ids = (const int32_t *)(d + o_slots);
-                p->d.merge_kind = (const int32_t *)(d + o_kind);
-                p->d.merge_cnt = (const int32_t *)(d + o_cnt);
-            }
-        } catch (...) {
-            st = GLM_ERR_ALLOC;
+        hipError_t e = hipGetDevice(&p->device);
+        st = e == hipSuccess ? upload_plan(p, (hipStream_t)hip_stream) : set_hip_error(e);
+        if (st != GLM_OK) {
+            release_plan_buffers(p);
             delete p;
             p = nullptr;
         }
@@ -611,13 +642,45 @@ glm_plan *glm_plan_create(glm_geom g, const int32_t *block_tables_host, int32_t 
     return p;
 }
 
+int glm_plan_rebuild(glm_plan *plan, glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
+                     const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B, void *hip_stream) {
+    if (!plan) return GLM_ERR_NULL;
+    if (!plan->dev) return GLM_ERR_PLAN_MISMATCH;               // a host-only plan has nothing to upload into
+    int st = GLM_OK;
+    glm_plan *fresh = plan_build(g, block_tables_host, max_blocks, seq_lens_host, q_lens_host, B, &st);
+    if (!fresh) return st;                                      // the plan is unchanged
+    int dev_now = -1;
+    hipError_t e = hipGetDevice(&dev_now);
+    if (e != hipSuccess || dev_now != plan->device) {
+        delete fresh;
+        return e != hipSuccess ? set_hip_error(e) : GLM_ERR_PLAN_MISMATCH;
+    }
+    // the new lists take the place of the old ones; the buffers stay
+    plan->g = fresh->g; plan->B = fresh->B; plan->max_blocks = fresh->max_blocks; plan->kind = fresh->kind;
+    for (int k = 0; k < 2; ++k) plan->chunks[k].swap(fresh->chunks[k]);
+    plan->members.swap(fresh->members);
+    plan->block_ids.swap(fresh->block_ids);
+    plan->slot_ids.swap(fresh->slot_ids);
+    plan->merge_kind.swap(fresh->merge_kind);
+    plan->merge_cnt.swap(fresh->merge_cnt);
+    plan->merge_stride = fresh->merge_stride;
+    plan->n_slots = fresh->n_slots;
+    plan->merge_by_token = fresh->merge_by_token;
+    plan->n_shared_segments = fresh->n_shared_segments;
+    plan->shared_blocks = fresh->shared_blocks;
+    delete fresh;
+    st = upload_plan(plan, (hipStream_t)hip_stream);
+    if (st != GLM_OK) {
+        // lists and device image no longer agree: the plan keeps no device side, attention calls reject it
+        release_plan_buffers(plan);
+        plan->d = DevicePlan{};
+    }
+    return st;
+}
+
 void glm_plan_destroy(glm_plan *plan) {
     if (!plan) return;
-    if (plan->dev) {
-        // the upload may still be in flight on the creating stream
-        (void)hipDeviceSynchronize();
-        (void)hipFree(plan->dev);
-    }
+    release_plan_buffers(plan);
     delete plan;
 }
 

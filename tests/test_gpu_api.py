@@ -38,6 +38,48 @@ def test_split_prefill_plan_needs_its_workspace():
     torch.cuda.synchronize()
 
 
+def test_plan_rebuild_in_place():
+    """One plan object rebuilt for a sequence of batches (more requests, fewer, another kind, a chunked prefill):
+    every result equals that of a freshly created plan bit for bit, and a call queued before a rebuild still runs
+    on the image it was queued with."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    mk = dict(num_q_heads=8, num_kv_heads=2, head_dim=128)
+    seq = [
+        W.custom_decode(5100, prefix_groups=[[0, 1, 2]], prefix_tokens=[96], suffix_tokens=[5, 40, 17, 300], **mk),
+        W.custom_decode(5101, prefix_groups=[list(range(40))], prefix_tokens=[640], suffix_tokens=list(range(3, 43)), **mk),
+        W.custom_prefill(5102, prefix_groups=[[0, 1]], prefix_tokens=[1504], q_lens=[200, 9], cached_suffix_tokens=[37, 900], **mk),
+        W.custom_decode(5103, prefix_groups=[], prefix_tokens=[], suffix_tokens=[700], **mk),
+        W.custom_prefill(5104, prefix_groups=[[0, 1, 2]], prefix_tokens=[64], q_lens=[33, 1, 20], **mk),
+    ]
+    devs = [gu.DeviceWorkload(w) for w in seq]
+
+    def run(dw, plan):
+        return dw.prefill(plan=plan) if dw.w.q_lens is not None else dw.decode(plan=plan)
+    fresh = [run(dw, dw.make_plan()) for dw in devs]
+    plan = devs[0].make_plan()
+    np.testing.assert_array_equal(run(devs[0], plan), fresh[0])
+    for k in (1, 2, 3, 4, 0, 1):
+        w = seq[k]
+        glm.glm_plan_rebuild(plan, w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+        np.testing.assert_array_equal(run(devs[k], plan), fresh[k], err_msg="after rebuilding for batch %d" % k)
+    # queued before the rebuild, finished after it (the plan is now that of batch 1)
+    d1, d3 = devs[1], devs[3]
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    d1.out.fill_(float("nan"))
+    torch.cuda.synchronize()
+    glm.glm_attn_decode(seq[1].geom, d1.pool, d1.q, d1.out, d1.tables, seq[1].max_blocks, d1.seq_lens, seq[1].B,
+                        seq[1].scale, plan, ws)
+    glm.glm_plan_rebuild(plan, seq[3].geom, seq[3].block_tables, seq[3].max_blocks, seq[3].seq_lens, None, seq[3].B)
+    got3 = d3.decode(plan=plan)
+    np.testing.assert_array_equal(d1.out.cpu().numpy().astype(np.float64), fresh[1])
+    np.testing.assert_array_equal(got3, fresh[3])
+    # a failed build leaves the plan as it was
+    bad = seq[3].seq_lens.copy(); bad[0] = seq[3].max_blocks * 16 + 1
+    assert glm.glm_plan_rebuild(plan, seq[3].geom, seq[3].block_tables, seq[3].max_blocks, bad, None, seq[3].B, check=False) == glm.GLM_ERR_RANGE
+    np.testing.assert_array_equal(d3.decode(plan=plan), fresh[3])
+
+
 @pytest.fixture
 def validate_env():
     old = os.environ.get("GLM_VALIDATE")

@@ -146,6 +146,13 @@ def test_cooperative_work_is_spread_over_all_xcds():
     assert min(per_xcd) == max(per_xcd) == 1024 * 4 // 128, per_xcd          # one kv head's row tiles per XCD
 
 
+def test_plan_rebuild_rejects_host_only_plans():
+    w = W.tiny_decode()
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    assert glm.glm_plan_rebuild(plan, w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B, hip_stream=0, check=False) == glm.GLM_ERR_PLAN_MISMATCH
+    assert len(plan.chunks()) > 0                                   # and leaves them as they were
+
+
 def _prefill_cover(w, plan):
     """Every (new token, head, visible block) is covered by exactly one entry of a prefill plan; returns the chunk
     starts per request."""
