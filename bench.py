@@ -77,6 +77,20 @@ def _time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def _step_stats(fn, steps):
+    """Median and shortest step, each step bracketed by its own pair of events on the launch stream (the binding
+    launches on torch's current stream)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        fn(i)
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    return {"median_ms": 0.5 * (t[(steps - 1) // 2] + t[steps // 2]), "min_ms": t[0], "steps": steps}
+
+
 def _kernel_times(glm, fn, steps):
     """Average duration per launch of each kernel kind, from events on the launch stream."""
     import torch
@@ -88,9 +102,9 @@ def _kernel_times(glm, fn, steps):
     glm.glm_profile_enable(False)
     out = {}
     for name, kid in glm.KERNEL_IDS.items():
-        ms, n = glm.glm_profile_read(kid)
+        ms, n, lo, med = glm.glm_profile_read_stats(kid)
         if n:
-            out[name] = {"avg_us": ms * 1e3 / n, "launches_per_step": n / steps}
+            out[name] = {"avg_us": ms * 1e3 / n, "median_us": med * 1e3, "min_us": lo * 1e3, "launches_per_step": n / steps}
     glm.glm_profile_reset()
     return out
 
@@ -122,6 +136,7 @@ def bench_decode(glm, w, layers, steps, warmup):
         glm.glm_attn_decode(g, pools[i % len(pools)], q, out, tables, w.max_blocks, lens, w.B, w.scale, plan, ws)
 
     ms = _time_steps(step, steps, warmup)
+    stats = _step_stats(step, min(steps, 128))
     kt = _kernel_times(glm, step, min(steps, 64))
     # the same call without a plan: every request streams its own K/V, shared blocks once per request
     ws_np = torch.empty(glm.glm_attn_workspace_bytes(g, w.B, 0, int(w.seq_lens.max())), dtype=torch.uint8, device="cuda")
@@ -150,7 +165,7 @@ def bench_decode(glm, w, layers, steps, warmup):
     kern_bytes = {"attn_stream_w1": tok[1] * per_tok, "attn_stream_w4": tok[4] * per_tok,
                   "attn_stream_fused": (tok[1] + tok[4]) * per_tok}
     res = {
-        "workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "plan_rebuild_ms": rebuild_ms,
+        "workload": w.name, "ms_per_step": ms, "step_events": stats, "plan_build_ms": plan_ms, "plan_rebuild_ms": rebuild_ms,
         "ms_per_step_if_plan_rebuilt_every_step": ms_rb,
         "ms_per_step_without_plan": ms_np, "speedup_from_streaming_shared_blocks_once": ms_np / ms,
         "layers_rotated": len(pools),

@@ -252,6 +252,9 @@ GLM_API int glm_last_hip_error(void); /* hipError_t of the most recent failing H
 GLM_API int glm_profile_enable(int on);
 GLM_API int glm_profile_reset(void);
 GLM_API int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches);
+/* The same, with the shortest and the median launch as well (any output pointer may be NULL). */
+GLM_API int glm_profile_read_stats(int kernel_id, double *total_ms, int64_t *launches, double *min_ms,
+                           double *median_ms);
 
 /*
  * Reference kernels for benchmarks (not part of the attention path).

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     glm_attn_decode, glm_attn_prefill_on_prefix, glm_kv_fork_copy, glm_kv_gather, glm_kv_append, glm_kv_gather_tokens,
     glm_plan_create, glm_plan_create_host, glm_plan_rebuild, glm_attn_workspace_bytes,
     glm_status_string, glm_version, glm_last_hip_error,
-    glm_profile_enable, glm_profile_reset, glm_profile_read, KERNEL_IDS,
+    glm_profile_enable, glm_profile_reset, glm_profile_read, glm_profile_read_stats, KERNEL_IDS,
     glm_bench_mfma, glm_bench_mfma_varied, glm_bench_copy, Cache, GLM_ERR_CACHE_FULL,
 )

@@ -27,7 +27,7 @@ EXPORTS = (
     "glm_plan_num_chunks", "glm_plan_get_chunks", "glm_plan_num_members", "glm_plan_get_members",
     "glm_plan_num_shared_segments", "glm_plan_shared_blocks", "glm_attn_workspace_bytes",
     "glm_status_string", "glm_version", "glm_last_hip_error",
-    "glm_profile_enable", "glm_profile_reset", "glm_profile_read", "glm_bench_mfma", "glm_bench_mfma_varied", "glm_bench_copy",
+    "glm_profile_enable", "glm_profile_reset", "glm_profile_read", "glm_profile_read_stats", "glm_bench_mfma", "glm_bench_mfma_varied", "glm_bench_copy",
     "glm_cache_create", "glm_cache_destroy", "glm_cache_acquire", "glm_cache_release", "glm_cache_end_session",
     "glm_cache_lookup", "glm_cache_block_tier", "glm_cache_drain_evicted", "glm_cache_stats",
 )
@@ -123,6 +123,9 @@ def _load() -> ctypes.CDLL:
     lib.glm_bench_copy.argtypes = [vp, vp, sz, vp]
     lib.glm_profile_enable.argtypes = [ctypes.c_int]
     lib.glm_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.glm_profile_read_stats.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.glm_profile_read_stats.restype = ctypes.c_int
     return lib
 
 
@@ -311,6 +314,14 @@ def glm_profile_read(kernel_id: int):
     ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(_lib.glm_profile_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)), "glm_profile_read")
     return ms.value, n.value
+
+
+def glm_profile_read_stats(kernel_id: int):
+    """(total milliseconds, launches, shortest launch ms, median launch ms) of one kernel kind since the last reset."""
+    ms, n, lo, med = ctypes.c_double(0.0), ctypes.c_int64(0), ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(_lib.glm_profile_read_stats(int(kernel_id), ctypes.byref(ms), ctypes.byref(n), ctypes.byref(lo), ctypes.byref(med)),
+           "glm_profile_read_stats")
+    return ms.value, n.value, lo.value, med.value
 
 
 def glm_bench_mfma(sink_dev, workgroups: int, iters: int, hip_stream=None) -> None:

@@ -1,5 +1,6 @@
 // Optional per-kernel timing with HIP events recorded on the stream each kernel is launched on.
 // Off by default: the hot calls then record nothing.
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 #include <vector>
@@ -48,10 +49,10 @@ int glm_profile_reset(void) {
     return GLM_OK;
 }
 
-int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches) {
+int glm_profile_read_stats(int kernel_id, double *total_ms, int64_t *launches, double *min_ms, double *median_ms) {
     std::lock_guard<std::mutex> lk(g_mu);
+    std::vector<float> t_all;
     double ms = 0.0;
-    int64_t n = 0;
     for (Sample &s : g_samples) {
         if (s.id != kernel_id) continue;
         hipError_t e = hipEventSynchronize(s.stop);
@@ -59,11 +60,19 @@ int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches) {
         if (e == hipSuccess) e = hipEventElapsedTime(&t, s.start, s.stop);
         if (e != hipSuccess) return set_hip_error(e);
         ms += t;
-        ++n;
+        t_all.push_back(t);
     }
+    std::sort(t_all.begin(), t_all.end());
+    const size_t n = t_all.size();
     if (total_ms) *total_ms = ms;
-    if (launches) *launches = n;
+    if (launches) *launches = (int64_t)n;
+    if (min_ms) *min_ms = n ? t_all[0] : 0.0;
+    if (median_ms) *median_ms = n ? 0.5 * (t_all[(n - 1) / 2] + t_all[n / 2]) : 0.0;
     return GLM_OK;
+}
+
+int glm_profile_read(int kernel_id, double *total_ms, int64_t *launches) {
+    return glm_profile_read_stats(kernel_id, total_ms, launches, nullptr, nullptr);
 }
 
 }  // extern "C"
