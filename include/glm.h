@@ -188,8 +188,9 @@ GLM_API glm_plan *glm_plan_create_host(glm_geom g, const int32_t *block_tables_h
 /*
  * Rebuilds a plan made by glm_plan_create in place: same arguments as glm_plan_create, all of which may differ
  * from those the plan was made with (batch size, table width, kind - q_lens_host NULL or not -, geometry):
- * the serving loop's call when the batch's block topology has changed (a request joined or left, a shared run was forked).  The plan's device
- * buffer and its pinned host image are reused when large enough, so the call costs the host-side build plus
+ * the serving loop's call when the batch's block topology has changed (a request joined or left, a shared run
+ * was forked).  The plan's device buffer and its pinned host image are reused when large enough, so the call
+ * costs the host-side build plus
  * one asynchronous copy on hip_stream - no allocation, no device-wide wait (measured: 0.04 ms against 0.48 ms
  * for glm_plan_create on 64 requests).  Ordering: the new image is copied on hip_stream, behind every launch
  * already queued there, so earlier calls with this plan on that stream still see the old image; work that uses
@@ -206,12 +207,13 @@ GLM_API size_t glm_plan_workspace_bytes(const glm_plan *plan);
 /* One entry of a plan's work list, for inspection and tests. */
 typedef struct {
     int32_t rep;      /* request whose block table is walked */
-    int32_t b0, b1;   /* logical blocks [b0, b1); b1 = INT32_MAX: to the end of the members' sequences */
+    int32_t b0, b1;   /* logical blocks [b0, b1); b1 = INT32_MAX: to the end of the members' sequences (prefill: as
+                         far as the rows of the tile see) */
     int32_t mem_off;  /* decode: offset of the member list; prefill: unused */
     int32_t n_mem;    /* decode: member requests; prefill: new tokens of rep; 0 = padding entry */
     int32_t row0;     /* first of the n_mem*(Hq/Hkv) rows this workgroup handles */
-    int32_t slot0;    /* where the members' partial-result slots are listed in the plan (member i: entry slot0 + i),
-                         or -1: writes the final output itself */
+    int32_t slot0;    /* where the members' partial-result slots are listed in the plan (member i, in a prefill plan
+                         new token i of rep: entry slot0 + i), or -1: writes the final output itself */
     int32_t ids_off;  /* offset of this run's physical block ids (copied from the tables when the plan was made) */
     int32_t n_ids;    /* how many of them; blocks appended later are looked up in the live table */
     int32_t waves;    /* 4: one workgroup of 4 waves shares the staged K/V over 128 rows; 1: one independent wave, 16 rows */
