@@ -1095,11 +1095,17 @@ using namespace glm;
 
 extern "C" {
 
+// wave items of a plan-less decode call per chunk: request x kv head x 16-row tile of the head group
+static int64_t implicit_waves_per_split(const glm_geom &g, int32_t B) {
+    const int G = g.num_q_heads / g.num_kv_heads;
+    return (int64_t)B * g.num_kv_heads * ((G + kRowsPerWave - 1) / kRowsPerWave);
+}
+
 size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, int32_t max_seq_len) {
     (void)sum_q;
     if (check_geom(g) != GLM_OK || B <= 0) return 256;
     int64_t splits = ((int64_t)std::max(max_seq_len, 1) + 255) / 256;
-    splits = std::min<int64_t>(std::max<int64_t>(splits, 1), kMaxImplicitSplits);
+    splits = std::min<int64_t>(std::max<int64_t>(splits, 1), max_implicit_splits(implicit_waves_per_split(g, B)));
     return std::max<size_t>(256, (size_t)B * splits * g.num_q_heads * (size_t)(g.head_dim + 2) * sizeof(float));
 }
 
@@ -1141,7 +1147,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
         n_slots = (size_t)plan->n_slots;
     } else {
         if (!workspace_dev || workspace_bytes < slot_bytes * (size_t)B) return GLM_ERR_WORKSPACE;
-        int64_t splits = std::min<int64_t>((int64_t)(workspace_bytes / (slot_bytes * (size_t)B)), kMaxImplicitSplits);
+        int64_t splits = std::min<int64_t>((int64_t)(workspace_bytes / (slot_bytes * (size_t)B)), max_implicit_splits(implicit_waves_per_split(g, B)));
         splits = std::min<int64_t>(splits, ((int64_t)max_blocks * kBlockSize + 255) / 256);
         splits = std::max<int64_t>(splits, 1);
         int32_t cb = (int32_t)((max_blocks + splits - 1) / splits);

@@ -1,6 +1,7 @@
 // Internal declarations shared by the host side and the kernels of libglm.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cstdint>
 #include <vector>
 
@@ -13,7 +14,11 @@ constexpr int kXcds = 8;              // L2 domains of the chip; workgroup i run
 constexpr int kRowsPerWave = 16;      // query rows (MFMA N) one wave owns
 constexpr int kBigWaves = 4;          // waves of a cooperative workgroup
 constexpr int kCoopRows = 128;        // query rows of a cooperative workgroup (32 per wave)
-constexpr int kMaxImplicitSplits = 32;
+// Most chunks a plan-less decode call cuts a request into: 32, or up to 128 where the batch is so small that
+// 32 would leave it below about 1024 wave items (one or two requests on long contexts).
+inline int max_implicit_splits(int64_t waves_per_split) {
+    return (int)std::min<int64_t>(128, std::max<int64_t>(32, 1024 / std::max<int64_t>(1, waves_per_split)));
+}
 
 enum PlanKind : int32_t { kDecode = 0, kPrefill = 1 };
 
