@@ -106,8 +106,11 @@ GLM_API int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_d
  *                      prefills, Sec. 6.1 serves them concurrently, are planned as split-K items like a decode
  *                      batch) and that of a small batch on long contexts (fewer 128-row tiles than the chip has
  *                      workgroup slots: the K/V range of each request is cut into chunks, one slot per
- *                      (new token, chunk), merged per token).  Without a plan, or when the plan has no partial
- *                      results, it is not read and may be NULL.
+ *                      (new token, chunk), merged per token).  Without a plan it is optional: given
+ *                      glm_attn_workspace_bytes(g, B, sum_q, longest sequence) bytes, a small batch on long
+ *                      contexts is cut into chunks in the same way (with the table width standing in for the
+ *                      lengths, which only a plan knows); with less, into fewer chunks or none.  A plan
+ *                      without partial results does not read it.
  * Errors as for glm_attn_decode; RANGE also covers q_len > seq_len and a cu_q_lens that does
  * not end at sum_q.  B == 0 or sum_q == 0 returns GLM_OK without a launch.
  */
@@ -233,7 +236,11 @@ GLM_API int32_t glm_plan_get_members(const glm_plan *plan, int32_t *out, int32_t
 GLM_API int32_t glm_plan_num_shared_segments(const glm_plan *plan);
 GLM_API int64_t glm_plan_shared_blocks(const glm_plan *plan);
 
-/* Recommended workspace for plan-less calls on up to B requests of up to max_seq_len tokens. */
+/*
+ * Recommended workspace for plan-less calls on up to B requests of up to max_seq_len tokens: sum_q == 0 for
+ * glm_attn_decode; for glm_attn_prefill_on_prefix the number of new tokens of the call (the result is then
+ * the space for cutting a small batch's K/V range into chunks, 256 if the batch is too large to be cut).
+ */
 GLM_API size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, int32_t max_seq_len);
 
 GLM_API const char *glm_status_string(int status);

@@ -62,6 +62,8 @@ struct MergeArgs {
     const int32_t *q_row_of;    // mixed batch: request -> its row of out (nullptr: r)
     int32_t q_rows;
     int32_t have_partials;      // the workspace holds partial slots (0: every request wrote its output itself)
+    const int32_t *cu_q_lens;   // plan-less prefill with K/V chunks: merge unit = (request, new token index below max_q_len)
+    int32_t max_q_len;
 };
 
 __device__ __forceinline__ int wave_max(int v) {
@@ -143,6 +145,7 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
     // ------------------------------------------------------------------ which work item
     glm_chunk c;
     int kvh;
+    int imp_split = 0;                  // plan-less prefill: which chunk of the K/V range
     const int G = a.G;
     if (a.mode == kPlanned) {
         // workgroup L runs on XCD L % 8 and takes the (L / 8)-th entry of that XCD's list.  An entry names
@@ -164,20 +167,24 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
     } else {
         // prefill without a plan: XCD x takes the (request, kv head) pairs x, x+8, .. (kv head fastest, so
         // that even a single request occupies every XCD), one pair after the other, its row tiles together
+        // With n_split > 1 (a small batch on long contexts) every pair's K/V range is cut into chunks of
+        // chunk_blocks blocks as well: new token t of the batch then leaves its partial of chunk s in slot
+        // t * n_split + s.
         const int x = L % kXcds;
         int k = L / kXcds;
         const int t = k % a.row_tiles; k /= a.row_tiles;
+        imp_split = k % a.n_split; k /= a.n_split;
         const int64_t pair = x + (int64_t)kXcds * k;
         if (pair >= (int64_t)a.B * a.Hkv) return;
         const int r = (int)(pair / a.Hkv);
         kvh = (int)(pair % a.Hkv);
         c.rep = r;
-        c.b0 = 0;
-        c.b1 = INT32_MAX;
+        c.b0 = imp_split * a.chunk_blocks;
+        c.b1 = imp_split == a.n_split - 1 ? INT32_MAX : c.b0 + a.chunk_blocks;
         c.mem_off = -1;
         c.n_mem = a.cu_q_lens[r + 1] - a.cu_q_lens[r];
         c.row0 = t * kCoopRows;
-        c.slot0 = -1;
+        c.slot0 = a.n_split > 1 ? 0 : -1;
         if (c.row0 >= c.n_mem * G) return;
     }
 
@@ -200,6 +207,7 @@ __device__ __forceinline__ void attn_coop_body(const AttnArgs &a, const glm_chun
         }
         // where this row's partial result goes (fetched now, beside the member list, and kept in a register)
         if (c.slot0 >= 0) part_slot = (c.mem_off >= 0 && a.slot_ids) ? a.slot_ids[c.slot0 + mi] : c.slot0 + mi;
+        if (a.mode == kImplicitPrefill) part_slot = (int)q_row * a.n_split + imp_split;
     }
     const int head = kvh * G + gh;
 
@@ -868,14 +876,29 @@ __global__ void __launch_bounds__(64 * NW) attn_merge_kernel(const MergeArgs a) 
     const int r = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int E = D / 64;
-    const int64_t out_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
+    int64_t unit = r;                  // whose slots are merged: unit * stride ..
+    int64_t out_row;
+    int n_token = 0;
+    if (a.cu_q_lens) {
+        // plan-less prefill: the grid covers max_q_len tokens per request; new token mi of request rr sees the
+        // chunks that start at or before its own position
+        const int rr = r / a.max_q_len, mi = r % a.max_q_len;
+        const int q0 = a.cu_q_lens[rr], q_len = a.cu_q_lens[rr + 1] - q0;
+        if (mi >= q_len) return;
+        unit = min(max(q0 + mi, 0), a.q_rows - 1);
+        out_row = unit;
+        const int pos = a.seq_lens[rr] - q_len + mi;
+        n_token = pos < 0 ? 0 : min(pos / (a.chunk_blocks * kBlockSize) + 1, a.n_split);
+    } else {
+        out_row = a.q_row_of ? min(max(a.q_row_of[r], 0), a.q_rows - 1) : r;
+    }
     float *dst = a.out + (out_row * a.Hq + h) * D + lane * E;
     // Request r owns the partial slots r * stride .. r * stride + n - 1, in merge order, so every address is
     // known from r alone: the (m, l) pairs of the first 64 partials and the first accumulator rows are
     // requested together with the count n, before n is known (slots at or beyond n hold stale data that is
     // never used: they are masked by selects, not by multiplication).
     const int stride = a.merge_kind ? a.merge_stride : a.n_split;
-    const int64_t row0 = ((int64_t)r * stride) * a.Hq + h;       // partial row of slot r * stride; next slot: + Hq
+    const int64_t row0 = (unit * stride) * a.Hq + h;             // partial row of the unit's first slot; next slot: + Hq
     auto fetch = [&](int i0, int cnt, float (&v)[8][E]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -906,6 +929,8 @@ __global__ void __launch_bounds__(64 * NW) attn_merge_kernel(const MergeArgs a) 
             }
             return;
         }
+    } else if (a.cu_q_lens) {
+        n = n_token;
     } else {
         const int nb = min((a.seq_lens[r] + kBlockSize - 1) / kBlockSize, a.max_blocks);
         n = min((nb + a.chunk_blocks - 1) / a.chunk_blocks, a.n_split);
@@ -1102,11 +1127,19 @@ static int64_t implicit_waves_per_split(const glm_geom &g, int32_t B) {
 }
 
 size_t glm_attn_workspace_bytes(glm_geom g, int32_t B, int32_t sum_q, int32_t max_seq_len) {
-    (void)sum_q;
     if (check_geom(g) != GLM_OK || B <= 0) return 256;
+    const size_t slot_bytes = (size_t)g.num_q_heads * (size_t)(g.head_dim + 2) * sizeof(float);
+    if (sum_q > 0) {
+        // a plan-less prefill call: one slot per (new token, K/V chunk) if the batch is small enough to be cut
+        const int G = g.num_q_heads / g.num_kv_heads;
+        const int64_t wgs = (((int64_t)sum_q * G + kCoopRows - 1) / kCoopRows) * g.num_kv_heads;
+        const int32_t nb = (int32_t)(((int64_t)std::max(max_seq_len, 1) + kBlockSize - 1) / kBlockSize);
+        const int64_t ns = choose_prefill_split(g, wgs, nb, sum_q);
+        return std::max<size_t>(256, ns > 1 ? (size_t)sum_q * (size_t)ns * slot_bytes : 0);
+    }
     int64_t splits = ((int64_t)std::max(max_seq_len, 1) + 255) / 256;
     splits = std::min<int64_t>(std::max<int64_t>(splits, 1), max_implicit_splits(implicit_waves_per_split(g, B)));
-    return std::max<size_t>(256, (size_t)B * splits * g.num_q_heads * (size_t)(g.head_dim + 2) * sizeof(float));
+    return std::max<size_t>(256, (size_t)B * splits * slot_bytes);
 }
 
 int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,
@@ -1285,10 +1318,43 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         if (max_q_len == 0) return GLM_OK;
         a.mode = kImplicitPrefill;
         const int64_t tiles = ((int64_t)max_q_len * G + kCoopRows - 1) / kCoopRows;
-        const int64_t grid = tiles * (((int64_t)B * Hkv + kXcds - 1) / kXcds) * kXcds;
-        if (grid > INT32_MAX) return GLM_ERR_GEOM;
+        // A small batch on long contexts is cut into K/V chunks like a planned one, as far as the workspace
+        // allows; the lengths are not known here, so the table width stands in for the longest request.
+        const size_t slot_bytes = (size_t)Hq * (size_t)(D + 2) * sizeof(float);
+        int64_t ns = choose_prefill_split(g, tiles * B * Hkv, max_blocks, sum_q);
+        if (!workspace_dev || !aligned16(workspace_dev)) ns = 1;
+        else ns = std::min<int64_t>(ns, (int64_t)(workspace_bytes / (slot_bytes * (size_t)sum_q)));
+        int32_t cb = max_blocks;
+        if (ns > 1) {
+            cb = (int32_t)std::max<int64_t>(prefill_min_chunk_blocks(), (max_blocks + ns - 1) / ns);
+            cb = (cb + 1) & ~1;
+            ns = (max_blocks + cb - 1) / cb;
+        }
+        a.n_split = (int32_t)std::max<int64_t>(ns, 1);
+        a.chunk_blocks = cb;
+        const int64_t grid = tiles * a.n_split * (((int64_t)B * Hkv + kXcds - 1) / kXcds) * kXcds;
+        if (grid > INT32_MAX || (int64_t)B * max_q_len * Hq > INT32_MAX) return GLM_ERR_GEOM;
         a.row_tiles = (int32_t)tiles;
+        if (a.n_split > 1) {
+            a.part_ml = (float *)workspace_dev;
+            a.part_acc = a.part_ml + (size_t)sum_q * a.n_split * (size_t)Hq * 2;
+        }
         e = launch_coop(D, a, grid, st);
+        if (e == hipSuccess && a.n_split > 1) {
+            MergeArgs m{};
+            m.out = (float *)out_dev;
+            m.seq_lens = seq_lens_dev;
+            m.Hq = Hq; m.max_blocks = max_blocks;
+            m.part_ml = a.part_ml;
+            m.part_acc = a.part_acc;
+            m.have_partials = 1;
+            m.n_split = a.n_split;
+            m.chunk_blocks = a.chunk_blocks;
+            m.cu_q_lens = cu_q_lens_dev;
+            m.max_q_len = max_q_len;
+            m.q_rows = sum_q;
+            e = launch_merge(D, m, (int)((int64_t)B * max_q_len * Hq), st);
+        }
     }
     return e == hipSuccess ? GLM_OK : set_hip_error(e);
 }

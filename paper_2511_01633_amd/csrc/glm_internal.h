@@ -54,6 +54,8 @@ private:
 
 int set_hip_error(hipError_t e);      // records e for glm_last_hip_error, returns GLM_ERR_HIP
 int check_geom(const glm_geom &g);
+int32_t prefill_min_chunk_blocks();   // shortest chunk a prefill request's K/V range is cut into
+int32_t choose_prefill_split(const glm_geom &g, int64_t workgroups, int32_t nb_max, int64_t sum_q);
 bool validate_enabled();
 
 }  // namespace glm

@@ -401,30 +401,13 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
     // A small batch (few new tokens on long contexts: an agent's short turn on a cached notebook, Sec. 5.2)
     // has fewer row tiles than the chip has workgroup slots, each walking a long run of keys.  Its K/V range
     // is then cut into chunks (split-K): every (row tile, chunk) is a workgroup that leaves partial results,
-    // one slot per (new token, chunk), merged per token afterwards.  The number of chunks minimises an
-    // estimate of the call's time: the longest walk (microseconds per block measured for one and for two
-    // workgroups per compute unit; beyond 512 workgroups they queue) plus what the partial results cost
-    // (written once, read once by the merge, at about 3 TB/s, and the merge launch itself).
+    // one slot per (new token, chunk), merged per token afterwards.
     int32_t want_split = 1;
-    const int forced = env_int("GLM_PLAN_PREFILL_SPLIT", -1);      // 0: never; n > 1: n chunks, whatever the estimate
-    const int32_t min_chunk = std::max(2, env_int("GLM_PLAN_PREFILL_MIN_CHUNK_BLOCKS", 16));
-    if (one_token.empty() && wgs > 0 && forced != 0) {
+    const int32_t min_chunk = prefill_min_chunk_blocks();
+    if (one_token.empty() && wgs > 0) {
         int32_t nb_max = 0;
         for (int32_t r = 0; r < B; ++r) nb_max = std::max(nb_max, ceil_div(seq_lens[r], kBlockSize));
-        const double width = p.g.head_dim == 64 ? 0.6 : 1.0;
-        const double slot_mb = (double)cu[B] * p.g.num_q_heads * (p.g.head_dim + 2) * 4e-6;
-        auto estimate = [&](int32_t ns) {
-            const double n_wg = (double)wgs * ns;
-            const double per_block = width * (n_wg <= 256 ? 0.27 : 0.45 * std::max(1.0, n_wg / 512.0));
-            return ceil_div(nb_max, ns) * per_block + (ns > 1 ? 6.0 + 2.0 * slot_mb * ns / 3.0 : 0.0);
-        };
-        double best = estimate(1) * 0.9;                            // a split has to promise a tenth at least
-        for (int32_t ns : {2, 3, 4, 6, 8, 12, 16, 24, 32}) {
-            if (ceil_div(nb_max, ns) < min_chunk) break;
-            const double t = estimate(ns);
-            if (t < best) { best = t; want_split = ns; }
-        }
-        if (forced > 1) want_split = std::min(forced, 32);
+        want_split = choose_prefill_split(p.g, wgs, nb_max, cu[B]);
     }
     std::vector<int32_t> chunk_of(B, 0), nchunks_of(B, 1);
     int32_t stride = 1;
@@ -579,6 +562,35 @@ void release_plan_buffers(glm_plan *p) {
 }
 
 }  // namespace
+
+int32_t prefill_min_chunk_blocks() { return std::max(2, env_int("GLM_PLAN_PREFILL_MIN_CHUNK_BLOCKS", 16)); }
+
+// Into how many chunks the K/V range of a small prefill batch is cut.  `workgroups` = row tiles x kv heads of the
+// uncut batch, `nb_max` = blocks of the longest request (or a bound), `sum_q` = new tokens.  Minimises an estimate
+// of the call's time: the longest walk (microseconds per block measured for one and for two workgroups per compute
+// unit; beyond 512 workgroups they queue) plus what the partial results cost (written once, read once by the
+// merge, at about 3 TB/s, and the merge launch itself).
+int32_t choose_prefill_split(const glm_geom &g, int64_t workgroups, int32_t nb_max, int64_t sum_q) {
+    const int forced = env_int("GLM_PLAN_PREFILL_SPLIT", -1);      // 0: never; n > 1: n chunks, whatever the estimate
+    if (forced == 0 || workgroups <= 0) return 1;
+    if (forced > 1) return std::min(forced, 32);
+    const int32_t min_chunk = prefill_min_chunk_blocks();
+    const double width = g.head_dim == 64 ? 0.6 : 1.0;
+    const double slot_mb = (double)sum_q * g.num_q_heads * (g.head_dim + 2) * 4e-6;
+    auto estimate = [&](int32_t ns) {
+        const double n_wg = (double)workgroups * ns;
+        const double per_block = width * (n_wg <= 256 ? 0.27 : 0.45 * std::max(1.0, n_wg / 512.0));
+        return ceil_div(nb_max, ns) * per_block + (ns > 1 ? 6.0 + 2.0 * slot_mb * ns / 3.0 : 0.0);
+    };
+    int32_t best_ns = 1;
+    double best = estimate(1) * 0.9;                                // a split has to promise a tenth at least
+    for (int32_t ns : {2, 3, 4, 6, 8, 12, 16, 24, 32}) {
+        if (ceil_div(nb_max, ns) < min_chunk) break;
+        const double t = estimate(ns);
+        if (t < best) { best = t; best_ns = ns; }
+    }
+    return best_ns;
+}
 
 int check_geom(const glm_geom &g) {
     if (g.num_blocks <= 0 || g.num_kv_heads <= 0 || g.num_q_heads <= 0) return GLM_ERR_GEOM;

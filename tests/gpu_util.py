@@ -43,10 +43,10 @@ class DeviceWorkload:
         torch.cuda.synchronize()
         return self.out.cpu().numpy().astype(np.float64)
 
-    def prefill(self, plan=None):
+    def prefill(self, plan=None, workspace=None):
         w = self.w
         self.out.fill_(float("nan"))
-        ws = None
+        ws = workspace
         if plan is not None and plan.workspace_bytes > 0:
             ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
         glm.glm_attn_prefill_on_prefix(w.geom, self.pool, self.q, self.out, self.tables, w.max_blocks, self.seq_lens,

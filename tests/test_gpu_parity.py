@@ -279,6 +279,57 @@ def test_prefill_cut_keys_other_shapes(case):
     _check(dw.prefill(plan=plan), ref, "chunked prefill, shape %d" % case)
 
 
+def _merge_launches(fn):
+    import paper_2511_01633_amd as glm
+    glm.glm_profile_reset()
+    glm.glm_profile_enable(True)
+    try:
+        out = fn()
+    finally:
+        glm.glm_profile_enable(False)
+    n = glm.glm_profile_read(glm.KERNEL_IDS["attn_merge"])[1]
+    glm.glm_profile_reset()
+    return out, n
+
+
+@pytest.mark.parametrize("case", range(5))
+def test_prefill_without_plan_cuts_keys_given_a_workspace(case):
+    """Without a plan the call knows no lengths, only the table width: given the recommended workspace it cuts a
+    small batch's K/V range into chunks all the same (one merge launch follows), with a smaller workspace into
+    fewer chunks, with none not at all - the result is the oracle's every time."""
+    import paper_2511_01633_amd as glm
+    shapes = [
+        dict(prefix_groups=[], prefix_tokens=[], q_lens=[33], cached_suffix_tokens=[5000], num_q_heads=4, num_kv_heads=1, head_dim=64),
+        dict(prefix_groups=[[0, 1, 3]], prefix_tokens=[1024], q_lens=[300, 3, 0, 17], cached_suffix_tokens=[900, 0, 40, 2500],
+             num_q_heads=6, num_kv_heads=2, head_dim=128),
+        dict(prefix_groups=[[0, 1]], prefix_tokens=[4000], q_lens=[2, 70], cached_suffix_tokens=[13, 1], num_q_heads=16,
+             num_kv_heads=2, head_dim=64),
+        dict(prefix_groups=[[1, 2]], prefix_tokens=[512], q_lens=[64, 64, 64], cached_suffix_tokens=[0, 3000, 10],
+             num_q_heads=8, num_kv_heads=8, head_dim=128),
+        dict(prefix_groups=[[0, 2]], prefix_tokens=[1504], q_lens=[700, 90, 9], cached_suffix_tokens=[37, 300, 1000],
+             num_q_heads=8, num_kv_heads=2, head_dim=128),
+    ]
+    gu = _gu()
+    w = W.custom_prefill(40 + case, **shapes[case])
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    full = glm.glm_attn_workspace_bytes(w.geom, w.B, w.sum_q, int(w.seq_lens.max()))
+    slot = w.geom.num_q_heads * (w.geom.head_dim + 2) * 4
+    assert full >= 2 * w.sum_q * slot, "the batch was expected to be small enough to be cut"
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    got, n_merge = _merge_launches(lambda: dw.prefill(plan=None, workspace=ws))
+    assert n_merge == 1
+    _check(got, ref, "plan-less chunked prefill, shape %d" % case)
+    # room for two chunks only, then for none
+    two = torch.empty(2 * w.sum_q * slot + 64, dtype=torch.uint8, device="cuda")
+    got2, n2 = _merge_launches(lambda: dw.prefill(plan=None, workspace=two))
+    assert n2 == 1
+    _check(got2, ref, "plan-less prefill, two chunks, shape %d" % case)
+    got1, n1 = _merge_launches(lambda: dw.prefill(plan=None, workspace=torch.empty(w.sum_q * slot, dtype=torch.uint8, device="cuda")))
+    assert n1 == 0
+    np.testing.assert_array_equal(got1, dw.prefill(plan=None))
+
+
 def test_prefill_without_any_cached_prefix_and_row_vs_decode():
     w = W.custom_prefill(3100, prefix_groups=[], prefix_tokens=[], q_lens=[4, 1, 37], num_q_heads=8, num_kv_heads=2,
                          head_dim=128)
