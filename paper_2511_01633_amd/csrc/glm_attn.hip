@@ -1274,43 +1274,51 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
         const size_t slot_bytes = (size_t)Hq * (size_t)(D + 2) * sizeof(float);
         if (merges && (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < (size_t)plan->n_slots * slot_bytes))
             return GLM_ERR_WORKSPACE;
-        if (plan->merge_by_token && (has_decode_rows || (int64_t)plan->merge_cnt.size() != (int64_t)sum_q))
-            return GLM_ERR_PLAN_MISMATCH;
+        if (plan->merge_by_token && (int64_t)plan->merge_cnt.size() != (int64_t)sum_q) return GLM_ERR_PLAN_MISMATCH;
         a.slot_ids = plan->d.slot_ids;
         if (merges) {
             a.part_ml = (float *)workspace_dev;
             a.part_acc = a.part_ml + (size_t)plan->n_slots * (size_t)Hq * 2;
         }
-        MergeArgs m{};
-        m.out = (float *)out_dev;
-        m.seq_lens = seq_lens_dev;
-        m.Hq = Hq; m.max_blocks = max_blocks;
-        m.part_ml = a.part_ml;
-        m.part_acc = a.part_acc;
-        m.have_partials = merges;
-        m.merge_kind = plan->d.merge_kind;
-        m.merge_cnt = plan->d.merge_cnt;
-        m.merge_stride = plan->merge_stride;
-        m.q_rows = sum_q;
-        if (!has_decode_rows) {
-            e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1], st);
-            // merge unit t is new token t, which is also its row of out
-            if (e == hipSuccess && plan->merge_by_token) e = launch_merge(D, m, (int64_t)sum_q * Hq, st);
-        } else {
-            // (the cooperative workgroups of a mixed batch's plan write their output themselves)
+        // The cooperative workgroups (prefill rows), then the wave-private ones (the one-token requests of a
+        // mixed batch), then the merge.  Two streaming launches, not the fused one: the cooperative workgroups
+        // write the prefill rows' output (tens of MB), and its way out of L2 at the end of their launch is hidden
+        // behind the wave-private launch; behind a fused launch it delays the merge (measured: 218 against
+        // 223 us per call).
+        // A batch whose prefill rows are cut into chunks is small, its cooperative workgroups write partial
+        // results only: there the fused launch wins.
+        if (has_decode_rows) {
             a.members = plan->d.members;
             a.block_ids = plan->d.block_ids;
             a.q_row_of = cu_q_lens_dev;
-            // Two launches, not the fused one: the cooperative workgroups write the prefill rows' output
-            // (tens of MB), and its way out of L2 at the end of their launch is hidden behind the wave-private
-            // launch; behind a fused launch it delays the merge (measured: 218 against 223 us per call).
+        }
+        if (has_decode_rows && plan->merge_by_token && plan->d.n_chunks[1] > 0 && fused_enabled()) {
+            a.chunks_priv = plan->d.chunks[0];
+            e = launch_fused(D, a, plan->d.n_chunks[1], plan->d.n_chunks[0], st);
+        } else {
             e = launch_coop(D, a, (int64_t)plan->d.n_chunks[1], st);
-            if (e == hipSuccess) {
+            if (e == hipSuccess && has_decode_rows) {
                 a.chunks = plan->d.chunks[0];
                 e = launch_private(D, a, (int64_t)(plan->d.n_chunks[0] / 4) * Hkv, st);
             }
-            if (e == hipSuccess) {
-                m.q_row_of = cu_q_lens_dev;
+        }
+        if (e == hipSuccess && merges) {
+            MergeArgs m{};
+            m.out = (float *)out_dev;
+            m.seq_lens = seq_lens_dev;
+            m.Hq = Hq; m.max_blocks = max_blocks;
+            m.part_ml = a.part_ml;
+            m.part_acc = a.part_acc;
+            m.have_partials = 1;
+            m.merge_kind = plan->d.merge_kind;
+            m.merge_cnt = plan->d.merge_cnt;
+            m.merge_stride = plan->merge_stride;
+            m.q_rows = sum_q;
+            if (plan->merge_by_token) {
+                // merge unit t is new token t, which is also its row of out
+                e = launch_merge(D, m, (int)((int64_t)sum_q * Hq), st);
+            } else {
+                m.q_row_of = cu_q_lens_dev;                  // merge unit r is request r
                 e = launch_merge(D, m, B * Hq, st);
             }
         }

@@ -191,9 +191,18 @@ std::vector<Work> pack_quads(std::vector<Item> &families, std::vector<Item> &sin
     return out;
 }
 
+// Merge units other than requests: in a mixed batch whose prefill rows are cut into chunks every new token of the
+// batch is a unit (a decode row's unit is its row of the output), and the slot stride is at least min_stride.
+struct MergeUnits {
+    const std::vector<int64_t> *unit_of;   // request -> its (first) unit
+    int64_t n_units;
+    int32_t min_stride;
+};
+
 // subset == nullptr: every request decodes.  Otherwise only the listed requests (the one-token rows of a mixed
 // batch) are planned here, everything goes to the wave-private launch, and the cooperative list is left alone.
-int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, const std::vector<int32_t> *subset = nullptr) {
+int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, const std::vector<int32_t> *subset = nullptr,
+                 const MergeUnits *units = nullptr) {
     const int32_t B = p.B, G = p.g.num_q_heads / p.g.num_kv_heads;
     std::vector<int32_t> nblk(B);
     for (int32_t r = 0; r < B; ++r) {
@@ -296,7 +305,10 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     // order), so the merging wave needs no list of slots: it knows all its addresses from r alone.
     int32_t stride = 1;
     for (int32_t r = 0; r < B; ++r) stride = std::max(stride, n_chunks_of[r]);
+    if (units) stride = std::max(stride, units->min_stride);
     p.merge_stride = stride;
+    auto unit_of = [&](int32_t r) -> int64_t { return units ? (*units->unit_of)[r] : r; };
+    const int64_t n_units = units ? units->n_units : B;
     for (auto &s : segs) {
         const int32_t nm = (int32_t)s.members.size();
         if (nm >= 2) { ++p.n_shared_segments; p.shared_blocks += s.b1 - s.b0; }
@@ -322,7 +334,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
                 slot0 = (int32_t)p.slot_ids.size();
                 for (int32_t mi = 0; mi < nm; ++mi) {
                     const int32_t r = s.members[mi];
-                    p.slot_ids.push_back(r * stride + n_partials[r]++);
+                    p.slot_ids.push_back((int32_t)(unit_of(r) * stride + n_partials[r]++));
                 }
             }
             const int32_t group = n_groups++;
@@ -366,14 +378,16 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
             if (last) break;
         }
     }
-    p.n_slots = p.slot_ids.empty() ? 0 : B * stride;
-    p.merge_cnt.assign(B, 0);
-    p.merge_kind.assign(B, kMergeList);
+    p.n_slots = p.slot_ids.empty() ? 0 : (int32_t)(n_units * stride);
+    p.merge_cnt.assign((size_t)n_units, 0);
+    p.merge_kind.assign((size_t)n_units, kMergeDirect);           // units nobody plans here: somebody else writes
     for (int32_t r = 0; r < B; ++r) {
-        p.merge_cnt[r] = n_partials[r];
-        if (!planned[r]) p.merge_kind[r] = kMergeDirect;          // somebody else writes (or there is nothing to write)
-        else if (nblk[r] == 0) p.merge_kind[r] = kMergeZero;
-        else if (n_partials[r] == 0) p.merge_kind[r] = kMergeDirect;
+        if (!planned[r]) continue;
+        const size_t u = (size_t)unit_of(r);
+        p.merge_cnt[u] = n_partials[r];
+        if (nblk[r] == 0) p.merge_kind[u] = kMergeZero;
+        else if (n_partials[r] == 0) p.merge_kind[u] = kMergeDirect;   // wrote its output itself
+        else p.merge_kind[u] = kMergeList;
     }
     std::vector<Work> quads = pack_quads(families, singles);
     p.chunks[0] = deal_to_xcds(quads, 4);
@@ -404,23 +418,46 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
     // one slot per (new token, chunk), merged per token afterwards.
     int32_t want_split = 1;
     const int32_t min_chunk = prefill_min_chunk_blocks();
-    if (one_token.empty() && wgs > 0) {
+    if (wgs > 0) {
         int32_t nb_max = 0;
-        for (int32_t r = 0; r < B; ++r) nb_max = std::max(nb_max, ceil_div(seq_lens[r], kBlockSize));
-        want_split = choose_prefill_split(p.g, wgs, nb_max, cu[B]);
+        int64_t new_tokens = 0;
+        for (int32_t r = 0; r < B; ++r) {
+            if (mixed && q_lens[r] == 1) continue;
+            nb_max = std::max(nb_max, ceil_div(seq_lens[r], kBlockSize));
+            new_tokens += q_lens[r];
+        }
+        want_split = choose_prefill_split(p.g, wgs, nb_max, new_tokens);
     }
     std::vector<int32_t> chunk_of(B, 0), nchunks_of(B, 1);
     int32_t stride = 1;
     for (int32_t r = 0; r < B; ++r) {
+        if (mixed && q_lens[r] == 1) continue;
         const int32_t nb = ceil_div(seq_lens[r], kBlockSize);
         int32_t cb = std::max(min_chunk, ceil_div(nb, want_split));
         cb = (cb + 1) & ~1;                                   // whole tiles of two blocks
         chunk_of[r] = cb;
         nchunks_of[r] = (want_split > 1 && q_lens[r] > 1) ? std::max(1, ceil_div(nb, cb)) : 1;
-        if (!(mixed && q_lens[r] == 1)) stride = std::max(stride, nchunks_of[r]);
+        stride = std::max(stride, nchunks_of[r]);
     }
     const bool split = stride > 1;
+    const int64_t sum_q = cu[B];
+    // The one-token requests of a mixed batch first (this clears and fills the slot lists).  If the prefill rows
+    // are cut into chunks the merge units of the whole batch are its new tokens, else they are the requests.
+    p.chunks[0].clear();
+    p.members.clear();
     p.slot_ids.clear();
+    p.merge_by_token = split;
+    if (!one_token.empty()) {
+        const MergeUnits units{&cu, sum_q, stride};
+        if (int st = build_decode(p, tables, seq_lens, &one_token, split ? &units : nullptr)) return st;
+        if (split) stride = p.merge_stride;                   // the decode rows may need more slots per unit
+    } else {
+        const size_t n_units = split ? (size_t)sum_q : (size_t)B;
+        p.merge_cnt.assign(n_units, 0);
+        p.merge_kind.assign(n_units, kMergeDirect);
+        p.merge_stride = stride;
+        p.n_slots = 0;
+    }
     std::vector<Work> work;
     for (int32_t r = 0; r < B; ++r) {
         if (mixed && q_lens[r] == 1) continue;
@@ -461,19 +498,11 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
             }
         }
     }
-    p.chunks[0].clear();
     p.chunks[1] = deal_to_xcds(work, 1);
-    p.members.clear();
-    p.merge_stride = stride;
-    p.merge_by_token = false;
     if (split) {
-        // one merge unit per new token: token t owns the slots t * stride .., its count is the number of chunks
-        // that start at or before its own position
-        const int64_t sum_q = cu[B];
-        p.merge_by_token = true;
+        // new token t owns the slots t * stride ..; its count is the number of chunks that start at or before its
+        // own position
         p.n_slots = (int32_t)(sum_q * stride);
-        p.merge_cnt.assign((size_t)sum_q, 0);
-        p.merge_kind.assign((size_t)sum_q, kMergeDirect);
         for (int32_t r = 0; r < B; ++r) {
             if (nchunks_of[r] <= 1) continue;
             const int64_t ctx = seq_lens[r] - q_lens[r];
@@ -483,14 +512,7 @@ int build_prefill(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, c
                 p.merge_kind[(size_t)(cu[r] + mi)] = kMergeList;
             }
         }
-        return GLM_OK;
     }
-    p.slot_ids.clear();
-    p.merge_cnt.assign(B, 0);
-    p.merge_stride = 1;
-    p.merge_kind.assign(B, kMergeDirect);
-    p.n_slots = 0;
-    if (!one_token.empty()) return build_decode(p, tables, seq_lens, &one_token);
     return GLM_OK;
 }
 

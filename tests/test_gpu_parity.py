@@ -473,6 +473,26 @@ def test_mixed_batch_plan_matches_oracle(d, hq, hkv):
     assert np.abs(noplan - ref).max() <= gu.TOL
 
 
+@pytest.mark.parametrize("d,hq,hkv,forced", [(128, 8, 2, None), (64, 8, 4, "5"), (128, 32, 8, None)])
+def test_mixed_batch_with_chunked_prefill_rows(d, hq, hkv, forced):
+    """A mixed batch whose prefill rows are few and sit on long contexts: their keys are cut into chunks, the merge
+    units of the whole call are its new tokens, and the one-token requests (split-K wave items with partial lists of
+    their own, some longer than the prefill rows' chunk count) are merged in the same launch."""
+    gu = _gu()
+    w = W.custom_prefill(8700 + d + hq, prefix_groups=[list(range(9))], prefix_tokens=[1536],
+                         q_lens=[1, 90, 1, 1, 37, 1, 0, 1, 1], cached_suffix_tokens=[300, 2000, 5, 5000, 17, 0, 40, 47, 1200],
+                         num_q_heads=hq, num_kv_heads=hkv, head_dim=d)
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan() if forced is None else _with_env("GLM_PLAN_PREFILL_SPLIT", forced, dw.make_plan)
+    ch = [c for c in plan.chunks() if c.n_mem]
+    assert any(c.waves == 1 for c in ch), "the one-token rows were expected as wave items"
+    assert any(c.waves == 4 and c.slot0 >= 0 and c.b0 > 0 for c in ch), "the prefill rows were expected to be cut"
+    got = dw.prefill(plan=plan)
+    _check(got, ref, "mixed batch, chunked prefill rows d=%d %d/%d" % (d, hq, hkv))
+    np.testing.assert_array_equal(dw.prefill(plan=plan), got)
+
+
 def test_all_one_token_prefill_equals_decode():
     gu = _gu()
     wd = W.custom_decode(8300, prefix_groups=[[0, 1, 2, 3, 4]], prefix_tokens=[128], suffix_tokens=[3, 200, 64, 0, 513],

@@ -232,6 +232,56 @@ def test_small_prefill_plans_cover_every_token_once(case, monkeypatch):
     assert max(len(v) for v in starts.values()) > 1, "the plan was expected to split"
 
 
+def test_mixed_plan_with_chunked_prefill_rows_covers_everything_once():
+    """One-token requests (wave items over their own prefix tree) beside few prefill rows on long contexts (cooperative
+    entries per chunk): every (request, new token, head, visible block) is covered exactly once, and the workspace
+    holds stride slots for every new token of the batch."""
+    w = W.custom_prefill(31, prefix_groups=[list(range(7))], prefix_tokens=[1536], q_lens=[1, 90, 1, 37, 1, 0, 1],
+                         cached_suffix_tokens=[300, 2000, 5, 17, 0, 40, 1200], num_q_heads=8, num_kv_heads=2, head_dim=128)
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    G = w.geom.group
+    members = plan.members()
+    seen = {}
+    n_partials = {}
+    for c in plan.chunks():
+        if c.n_mem == 0:
+            continue
+        if c.waves == 4:
+            r = c.rep
+            assert w.q_lens[r] > 1 and c.n_mem == w.q_lens[r]
+            ctx = int(w.seq_lens[r] - w.q_lens[r])
+            for rho in range(c.row0, min(c.n_mem * G, c.row0 + 128)):
+                mi, gh = rho // G, rho % G
+                nb = -(-(ctx + mi + 1) // 16)
+                end = nb if c.b1 == 2 ** 31 - 1 else min(c.b1, nb)
+                for b in range(c.b0, end):
+                    key = (r, mi, c.kvh * G + gh, b)
+                    seen[key] = seen.get(key, 0) + 1
+        else:
+            mem = members[c.mem_off:c.mem_off + c.n_mem]
+            assert all(w.q_lens[r] == 1 for r in mem) and c.kvh == -1
+            for rho in range(c.row0, min(c.n_mem * G, c.row0 + 16)):
+                r, gh = int(mem[rho // G]), rho % G
+                nb = -(-int(w.seq_lens[r]) // 16)
+                end = nb if c.b1 == 2 ** 31 - 1 else min(c.b1, nb)
+                for b in range(c.b0, end):
+                    for kvh in range(w.geom.num_kv_heads):
+                        key = (r, 0, kvh * G + gh, b)
+                        seen[key] = seen.get(key, 0) + 1
+                if gh == 0 and c.slot0 >= 0:
+                    n_partials[r] = n_partials.get(r, 0) + 1
+    want = 0
+    for r in range(w.B):
+        ctx = int(w.seq_lens[r] - w.q_lens[r])
+        for mi in range(int(w.q_lens[r])):
+            want += -(-(ctx + mi + 1) // 16) * w.geom.num_q_heads
+    assert len(seen) == want and set(seen.values()) == {1}
+    starts = sorted({c.b0 for c in plan.chunks() if c.n_mem and c.waves == 4 and c.rep == 1})
+    assert len(starts) > 1, "the prefill rows were expected to be cut"
+    stride = max([len(starts)] + list(n_partials.values()))
+    assert plan.workspace_bytes == w.sum_q * stride * w.geom.num_q_heads * (128 + 2) * 4
+
+
 def test_plan_handles_partial_sharing_and_unequal_lengths():
     # request 1 ends inside the run shared with request 0; request 2 shares only the first block
     tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)
