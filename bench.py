@@ -308,8 +308,10 @@ def bench_short_turn(glm, w, steps, warmup):
     pool, q, tables, lens, cu = _dev(w.pool), _dev(w.q), _dev(w.block_tables), _dev(w.seq_lens), _dev(w.cu_q_lens)
     out = torch.empty((w.sum_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
     mq = int(w.q_lens.max())
-    res = {"workload": w.name, "requests": int(w.B), "new_tokens": [int(x) for x in w.q_lens],
-           "seq_lens": [int(x) for x in w.seq_lens], "flops": w.flops(), "unique_kv_bytes": w.unique_kv_bytes()}
+    many = np.flatnonzero(w.q_lens != 1)
+    res = {"workload": w.name, "requests": int(w.B), "one_token_requests": int((w.q_lens == 1).sum()),
+           "new_tokens": [int(w.q_lens[r]) for r in many], "seq_lens": [int(w.seq_lens[r]) for r in many],
+           "flops": w.flops(), "unique_kv_bytes": w.unique_kv_bytes()}
     for name, flag in (("keys_cut_into_chunks", None), ("one_workgroup_per_row_tile", "0")):
         old = os.environ.get("GLM_PLAN_PREFILL_SPLIT")
         if flag is not None:
@@ -330,7 +332,7 @@ def bench_short_turn(glm, w, steps, warmup):
         ent = [c for c in plan.chunks() if c.n_mem]
         res[name] = {"ms_per_step": ms, "kernels": _kernel_times(glm, step, min(steps, 16)), "TFLOPs": w.flops() / ms / 1e9,
                      "GBps_unique": (w.unique_kv_bytes() + w.q.nbytes + out.numel() * 4) / ms / 1e6,
-                     "workgroups": len(ent), "chunks_per_request": len({c.b0 for c in ent if c.rep == 0}),
+                     "workgroups": len(ent), "chunks_per_request": len({c.b0 for c in ent if c.waves == 4 and c.rep == int(many[0])}),
                      "workspace_bytes": int(plan.workspace_bytes)}
     res["speedup_from_cutting_keys"] = res["one_workgroup_per_row_tile"]["ms_per_step"] / res["keys_cut_into_chunks"]["ms_per_step"]
     return res
@@ -471,6 +473,7 @@ def main():
             extra["mixed_batch"] = bench_mixed(glm, W.mixed_batch(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "short" in only:
             extra["short_turn_prefill"] = bench_short_turn(glm, W.short_turn_prefill(), max(10, args.steps // 4), max(2, args.warmup // 4))
+            extra["mixed_short_turns"] = bench_short_turn(glm, W.mixed_short_turns(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "qwen3" in only:
             extra["qwen3_moe_decode"] = bench_decode(glm, W.qwen3_moe_decode(), args.layers, max(10, args.steps // 2),
                                                      max(2, args.warmup // 2))

@@ -387,6 +387,18 @@ def test_short_turn_prefill_full():
     _check(dw.prefill(plan=None), ref, "short_turn_prefill (no plan)")
 
 
+def test_mixed_short_turns_full():
+    """The benchmark's short turns in the middle of a decode batch, as timed (prefill rows cut into chunks, fused
+    launch, one merge over the new tokens of the whole call): every row against the oracle."""
+    gu = _gu()
+    w = W.mixed_short_turns()
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    ch = [c for c in plan.chunks() if c.n_mem]
+    assert any(c.waves == 4 and c.slot0 >= 0 and c.b0 > 0 for c in ch) and any(c.waves == 1 for c in ch)
+    _check(dw.prefill(plan=plan), _oracle(w), "mixed_short_turns (plan)")
+
+
 def test_tree_decode_70b_full_sampled():
     gu = _gu()
     w = W.tree_decode_70b()

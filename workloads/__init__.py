@@ -24,6 +24,7 @@ from .gen import (  # noqa: F401
     qwen3_moe_decode,
     mixed_batch,
     short_turn_prefill,
+    mixed_short_turns,
     prefill_on_prefix,
     tree_decode_70b,
     eviction_churn,

@@ -374,6 +374,24 @@ def short_turn_prefill(seed: Optional[int] = None, *, branches: int = 2, prefix_
                           name="short_turn_prefill")
 
 
+def mixed_short_turns(seed: Optional[int] = None, *, prefill_branches: int = 2, decode_branches: int = 64,
+                      prefix_tokens: int = 2048, cached_lo: int = 4000, cached_hi: int = 6000, q_lo: int = 64,
+                      q_hi: int = 192, suffix_lo: int = 128, suffix_hi: int = 1024) -> Workload:
+    """Short turns on long cached contexts in the middle of a decode batch: on one shared cached prefix,
+    `prefill_branches` branches append U{q_lo..q_hi} new tokens after U{cached_lo..cached_hi} cached tokens of
+    their own, and `decode_branches` branches with a cached private suffix of U{suffix_lo..suffix_hi} tokens append
+    one (concurrent agents in different phases, Sec. 6.1).  Llama-3-8B attention shape."""
+    seed = config_seed(8) if seed is None else seed
+    r2 = _rng(seed ^ 0x5EED)
+    B = prefill_branches + decode_branches
+    kind = np.zeros(B, bool)
+    kind[r2.permutation(B)[:prefill_branches]] = True
+    q_lens = [int(r2.integers(q_lo, q_hi + 1)) if kind[r] else 1 for r in range(B)]
+    sfx = [int(r2.integers(cached_lo, cached_hi + 1)) if kind[r] else int(r2.integers(suffix_lo, suffix_hi + 1)) for r in range(B)]
+    return custom_prefill(seed, prefix_groups=[list(range(B))], prefix_tokens=[prefix_tokens], q_lens=q_lens,
+                          cached_suffix_tokens=sfx, num_q_heads=32, num_kv_heads=8, head_dim=128, name="mixed_short_turns")
+
+
 def tree_decode_70b(seed: Optional[int] = None, *, root_tokens: int = 8192, mids: int = 8, mid_tokens: int = 1024,
                     leaves_per_mid: int = 32, suffix_tokens: int = 256, num_q_heads: int = 64,
                     num_kv_heads: int = 8, head_dim: int = 128, block_size: int = 16) -> Workload:
