@@ -197,7 +197,8 @@ GLM_API glm_plan *glm_plan_create_host(glm_geom g, const int32_t *block_tables_h
  * one asynchronous copy on hip_stream - no allocation, no device-wide wait (measured: 0.04 ms against 0.48 ms
  * for glm_plan_create on 64 requests).  Ordering: the new image is copied on hip_stream, behind every launch
  * already queued there, so earlier calls with this plan on that stream still see the old image; work that uses
- * the plan on OTHER streams must have finished.  The call waits on the host for the plan's previous upload only.
+ * the plan on OTHER streams must have finished, and no other host thread may be inside a call that takes this
+ * plan.  The call waits on the host for the plan's previous upload only.
  * Returns GLM_OK, or the status of the failed build (RANGE / GEOM / NULL / ALLOC; the plan is then unchanged),
  * GLM_ERR_PLAN_MISMATCH for a host-only plan or another current device, GLM_ERR_HIP if a buffer had to grow
  * and could not (the plan then has no device side left and attention calls reject it).
