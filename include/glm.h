@@ -81,6 +81,9 @@ typedef struct glm_plan glm_plan;
  *                      glm_attn_workspace_bytes with the real bound is the recommended size)
  * Errors: NULL / GEOM / ALIGN / WORKSPACE / PLAN_MISMATCH / HIP; RANGE under GLM_VALIDATE=1
  * (block id outside the pool, seq_len > max_blocks*bs; needs a device-to-host copy and a sync).
+ * A plan holds copies of the block ids of its runs: with tables that changed in any other way than
+ * described above the call would read the old blocks.  GLM_VALIDATE=1 compares them and returns
+ * GLM_ERR_PLAN_MISMATCH instead; without it the caller is trusted.
  * B == 0 returns GLM_OK without a launch.
  */
 GLM_API int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void *out_dev,

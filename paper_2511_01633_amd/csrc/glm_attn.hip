@@ -1084,8 +1084,10 @@ hipError_t launch_merge(int D, const MergeArgs &m, int grid, hipStream_t st) {
 }
 
 // Debug-only range checks on the device inputs (GLM_VALIDATE=1): copies them back and syncs.
+// With a plan it also checks what the plan assumes: every block id it copied from the tables is still the one the
+// tables of its members hold (for the blocks a member can see), and a prefill plan's new-token counts are the call's.
 int validate_inputs(const glm_geom &g, const int32_t *tables_dev, int32_t max_blocks, const int32_t *seq_lens_dev,
-                    const int32_t *cu_dev, int32_t B, int32_t sum_q, hipStream_t st) {
+                    const int32_t *cu_dev, int32_t B, int32_t sum_q, const glm_plan *plan, hipStream_t st) {
     try {
         std::vector<int32_t> tables((size_t)B * max_blocks), lens(B), cu(cu_dev ? B + 1 : 0);
         hipError_t e = hipStreamSynchronize(st);
@@ -1106,6 +1108,28 @@ int validate_inputs(const glm_geom &g, const int32_t *tables_dev, int32_t max_bl
                 const int32_t id = tables[(size_t)r * max_blocks + b];
                 if (id < 0 || id >= g.num_blocks) return GLM_ERR_RANGE;
             }
+        }
+        if (plan) {
+            for (int kind = 0; kind < 2; ++kind)
+                for (const glm_chunk &c : plan->chunks[kind]) {
+                    if (c.n_mem == 0) continue;
+                    if (c.rep < 0 || c.rep >= B) return GLM_ERR_PLAN_MISMATCH;
+                    if (cu_dev && c.waves == kBigWaves) {            // a prefill row tile: rep's new tokens
+                        if (c.n_mem != cu[c.rep + 1] - cu[c.rep]) return GLM_ERR_PLAN_MISMATCH;
+                        continue;                                   // (its block ids are read from the live table)
+                    }
+                    if (c.mem_off < 0 || (size_t)c.mem_off + (size_t)c.n_mem > plan->members.size() || c.ids_off < 0 ||
+                        (size_t)c.ids_off + (size_t)c.n_ids > plan->block_ids.size())
+                        return GLM_ERR_PLAN_MISMATCH;
+                    for (int32_t mi = 0; mi < c.n_mem; ++mi) {
+                        const int32_t r = plan->members[(size_t)c.mem_off + mi];
+                        if (r < 0 || r >= B) return GLM_ERR_PLAN_MISMATCH;
+                        const int64_t nb = ((int64_t)lens[r] + kBlockSize - 1) / kBlockSize;
+                        for (int32_t i = 0; i < c.n_ids && c.b0 + i < nb; ++i)
+                            if (tables[(size_t)r * max_blocks + c.b0 + i] != plan->block_ids[(size_t)c.ids_off + i])
+                                return GLM_ERR_PLAN_MISMATCH;
+                    }
+                }
         }
     } catch (...) {
         return GLM_ERR_ALLOC;
@@ -1197,7 +1221,7 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
     m.have_partials = n_slots > 0;
 
     if (validate_enabled())
-        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, nullptr, B, 0, st)) return v;
+        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, nullptr, B, 0, plan, st)) return v;
 
     hipError_t e = hipSuccess;
     if (plan) {
@@ -1260,7 +1284,7 @@ int glm_attn_prefill_on_prefix(glm_geom g, const void *kv_pool_dev, const void *
     a.scale_log2 = scale * 1.44269504088896340736f;
 
     if (validate_enabled())
-        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, cu_q_lens_dev, B, sum_q, st)) return v;
+        if (int v = validate_inputs(g, block_tables_dev, max_blocks, seq_lens_dev, cu_q_lens_dev, B, sum_q, plan, st)) return v;
 
     hipError_t e;
     if (plan) {

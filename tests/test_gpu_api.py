@@ -124,6 +124,46 @@ def test_validate_rejects_bad_tables_and_lengths(validate_env):
     torch.cuda.synchronize()
 
 
+def test_validate_rejects_a_plan_that_no_longer_matches_the_tables(validate_env):
+    """A plan copies the block ids of its runs; under GLM_VALIDATE=1 a call whose tables have changed underneath it
+    (other than by growing a private tail) is refused instead of reading the old blocks."""
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(5200, prefix_groups=[[0, 1, 2]], prefix_tokens=[64], suffix_tokens=[30, 9, 20, 50], num_q_heads=8,
+                        num_kv_heads=2, head_dim=128, extra_table_cols=2)
+    dw = gu.DeviceWorkload(w)
+    plan = dw.make_plan()
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+
+    def call(tables, lens):
+        return glm.glm_attn_decode(w.geom, dw.pool, dw.q, dw.out, tables, w.max_blocks, lens, w.B, w.scale, plan, ws,
+                                   check=False)
+    assert call(dw.tables, dw.seq_lens) == glm.GLM_OK
+    # a private tail that grew by a block (any free id) and a token: still this plan's batch
+    grown_t, grown_l = w.block_tables.copy(), w.seq_lens.copy()
+    nb1 = -(-int(w.seq_lens[1]) // 16)
+    used = set(int(x) for r in range(w.B) for x in w.block_tables[r, :-(-int(w.seq_lens[r]) // 16)])
+    free = next(i for i in range(w.geom.num_blocks) if i not in used)
+    grown_t[1, nb1] = free
+    grown_l[1] = nb1 * 16 + 1
+    assert call(gu.dev(grown_t), gu.dev(grown_l)) == glm.GLM_OK
+    # request 2 forked away from the shared prefix (its second block now lives elsewhere): the plan is stale
+    forked = w.block_tables.copy()
+    forked[2, 1] = free
+    assert call(gu.dev(forked), dw.seq_lens) == glm.GLM_ERR_PLAN_MISMATCH
+    torch.cuda.synchronize()
+    # a prefill plan belongs to its new-token counts
+    wp = W.custom_prefill(5201, prefix_groups=[[0, 1]], prefix_tokens=[64], q_lens=[20, 30], num_q_heads=8, num_kv_heads=2,
+                          head_dim=128)
+    dp = gu.DeviceWorkload(wp)
+    pp = dp.make_plan()
+    other_cu = gu.dev(np.array([0, 25, 50], np.int32))
+    st = glm.glm_attn_prefill_on_prefix(wp.geom, dp.pool, dp.q, dp.out, dp.tables, wp.max_blocks, dp.seq_lens, other_cu, wp.B,
+                                        wp.sum_q, 30, wp.scale, pp, None, check=False)
+    assert st == glm.GLM_ERR_PLAN_MISMATCH
+    torch.cuda.synchronize()
+
+
 def test_validate_rejects_bad_copy_lists(validate_env):
     gu = _gu()
     import paper_2511_01633_amd as glm
