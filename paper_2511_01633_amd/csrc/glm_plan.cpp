@@ -42,23 +42,34 @@ void build_segments(const int32_t *tables, int32_t max_blocks, const std::vector
                 if (nblk[m[0]] > f.start) out.push_back({m, f.start, nblk[m[0]], true});
                 break;
             }
-            size_t active = 0;
-            for (int32_t r : m) active += nblk[r] > i;
-            if (active == 0) {
+            // how far all members stay alive and hold the same ids: each row is compared with the first member's
+            // in one sequential pass (the tables are row-major; a walk block by block over all members would
+            // touch a new cache line per member and block)
+            int32_t alive = INT32_MAX;
+            for (int32_t r : m) alive = std::min(alive, nblk[r]);
+            if (alive > i) {
+                const int32_t *row0 = tables + (int64_t)m[0] * max_blocks;
+                int32_t upto = alive;
+                for (size_t k = 1; k < m.size() && upto > i; ++k) {
+                    const int32_t *row = tables + (int64_t)m[k] * max_blocks;
+                    int32_t j = i;
+                    while (j < upto && row[j] == row0[j]) ++j;
+                    upto = j;
+                }
+                i = upto;
+            }
+            if (i >= alive) {                                       // a member ends here
+                size_t active = 0;
+                for (int32_t r : m) active += nblk[r] > i;
                 if (i > f.start) out.push_back({m, f.start, i, false});
+                if (active > 0) {
+                    std::vector<int32_t> rest;
+                    for (int32_t r : m) if (nblk[r] > i) rest.push_back(r);
+                    stack.push_back({std::move(rest), i});
+                }
                 break;
             }
-            if (active < m.size()) {
-                if (i > f.start) out.push_back({m, f.start, i, false});
-                std::vector<int32_t> rest;
-                for (int32_t r : m) if (nblk[r] > i) rest.push_back(r);
-                stack.push_back({std::move(rest), i});
-                break;
-            }
-            const int32_t id0 = tables[(int64_t)m[0] * max_blocks + i];
-            bool same = true;
-            for (int32_t r : m) same &= tables[(int64_t)r * max_blocks + i] == id0;
-            if (same) { ++i; continue; }
+            // the members' ids differ at block i
             if (i > f.start) out.push_back({m, f.start, i, false});
             // partition by physical id at logical block i, keeping request order inside a part
             std::vector<std::pair<int32_t, int32_t>> keyed;
