@@ -253,11 +253,28 @@ def bench_churn(glm, W, w, steps, warmup, variants=4):
 
     ms = _time_steps(step, steps, warmup)
     kt = _kernel_times(glm, step, min(steps, 16))
+
+    # the same step with the plan's cost inside the timed loop: the tables change every 8 steps and one plan object
+    # is rebuilt in place for them
+    plan_rb = glm.glm_plan_create(g, var[0]["st"].block_tables, w.max_blocks, w.seq_lens, None, w.B)
+
+    def step_rb(i):
+        v = var[(i // 8) % variants]
+        if i % 8 == 0:
+            glm.glm_plan_rebuild(plan_rb, g, v["st"].block_tables, w.max_blocks, w.seq_lens, None, w.B)
+        pool = pools[i % 2]
+        glm.glm_kv_fork_copy(g, pool, v["fsrc"], v["fdst"], v["fn"], v["st"].fork_src.size)
+        glm.glm_kv_gather(g, pool, v["ev"], staging, None, v["st"].evict_ids.size)
+        glm.glm_kv_gather(g, staging, None, pool, v["re"], v["st"].readmit_ids.size)
+        glm.glm_attn_decode(g, pool, q, out, v["tables"], w.max_blocks, lens, w.B, w.scale, plan_rb, ws)
+
+    ms_rb = _time_steps(step_rb, steps, warmup)
     kv = w.unique_kv_bytes()
     blk = g.block_bytes
     gather_bytes = 2 * blk * sum(v["st"].evict_ids.size for v in var) / variants      # read + write per gather
     fork_bytes = 2 * sum(int(v["st"].fork_ntok.sum()) for v in var) / variants * 2 * g.num_kv_heads * g.head_dim * 2
-    res = {"workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms, "unique_kv_bytes": kv,
+    res = {"workload": w.name, "ms_per_step": ms, "plan_build_ms": plan_ms,
+           "ms_per_step_plan_rebuilt_every_8_steps": ms_rb, "unique_kv_bytes": kv,
            "GBps_step": (kv + 2 * gather_bytes + fork_bytes) / ms / 1e6, "tokens_per_s_per_layer": w.B / ms * 1e3,
            "kernels": kt, "gather_bytes_per_launch": gather_bytes, "fork_bytes_per_launch": fork_bytes}
     if "kv_gather" in kt:
