@@ -417,6 +417,33 @@ def test_tree_decode_70b_full_sampled():
     _check(got_np[req, head], ref, "tree_decode_70b without a plan (256 sampled rows)")
 
 
+def _permuted(w, seed):
+    """The same batch with its blocks at other physical ids (pool permuted, tables remapped)."""
+    perm = np.random.default_rng(seed).permutation(w.geom.num_blocks)
+    pool = np.empty_like(w.pool)
+    pool[perm] = w.pool
+    tables = np.where(w.block_tables >= 0, perm[np.clip(w.block_tables, 0, None)], -1).astype(np.int32)
+    return W.Workload(w.name + "_permuted", w.geom, pool, w.q, tables, w.seq_lens, w.scale, q_lens=w.q_lens,
+                      cu_q_lens=w.cu_q_lens)
+
+
+@pytest.mark.parametrize("name", ["tree_decode_70b", "prefill_on_prefix", "mixed_short_turns"])
+def test_full_size_result_does_not_depend_on_physical_placement(name):
+    """A property that holds at any size: where the blocks lie in the pool changes neither the plan (it depends on
+    which ids are equal, not on their values) nor the order of any sum, so the output bits are the same.  Covers the
+    fused decode launch, the cooperative prefill launch and the chunked mixed call at the benchmark's sizes."""
+    gu = _gu()
+    w = getattr(W, name)()
+    run = (lambda d: d.decode(plan=d.make_plan())) if w.q_lens is None else (lambda d: d.prefill(plan=d.make_plan()))
+    dw = gu.DeviceWorkload(w)
+    got = run(dw)
+    del dw
+    torch.cuda.empty_cache()
+    got_p = run(gu.DeviceWorkload(_permuted(w, 77)))
+    assert np.isfinite(got).all()
+    np.testing.assert_array_equal(got_p, got)
+
+
 def test_eviction_churn_step_full_sampled():
     """One churn step: fork copy-on-write of partly filled last blocks, eviction of 2 % of the live
     blocks to a staging buffer and re-admission into other free slots, then decode on the new tables."""
