@@ -417,6 +417,54 @@ def test_tree_decode_70b_full_sampled():
     _check(got_np[req, head], ref, "tree_decode_70b without a plan (256 sampled rows)")
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_seeded_random_batches_against_oracle(seed):
+    """Seeded random batches over everything the planner distinguishes: batch size, head grouping and size, shared
+    prefix groups, requests with no, one or many new tokens, short and long cached contexts, and (every other seed)
+    a forced number of key chunks.  Prefill with a plan, without one, and - when every request has one new token -
+    as a decode call with and without a plan: the oracle's result every time."""
+    gu = _gu()
+    rng = np.random.default_rng(9000 + seed)
+    hkv = int(rng.choice([1, 2, 4]))
+    hq = hkv * int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 10))
+    kinds = rng.choice(["decode", "few", "mixed"], p=[0.25, 0.35, 0.4])
+    q_lens = []
+    for _ in range(B):
+        if kinds == "decode":
+            q_lens.append(1)
+        elif kinds == "few":
+            q_lens.append(int(rng.choice([0, 2, 17, 60, 130])))
+        else:
+            q_lens.append(int(rng.choice([1, 1, 1, 0, 33, 150])))
+    groups, rest = [], list(range(B))
+    rng.shuffle(rest)
+    while len(rest) >= 2 and rng.random() < 0.7:
+        n = int(rng.integers(2, len(rest) + 1))
+        groups.append(sorted(rest[:n])); rest = rest[n:]
+    prefix_tokens = [int(rng.choice([16, 64, 400, 1504])) for _ in groups]
+    suffix = [int(rng.choice([0, 5, 300, 1000, 2500])) for _ in range(B)]
+    w = W.custom_prefill(9100 + seed, prefix_groups=groups, prefix_tokens=prefix_tokens, q_lens=q_lens,
+                         cached_suffix_tokens=suffix, num_q_heads=hq, num_kv_heads=hkv, head_dim=d)
+    ref = _oracle(w)
+    dw = gu.DeviceWorkload(w)
+    what = "seed %d: B=%d %d/%d d%d q=%s" % (seed, B, hq, hkv, d, q_lens)
+    if w.sum_q:
+        forced = str(int(rng.integers(2, 9))) if seed % 2 else None
+        plan = dw.make_plan() if forced is None else _with_env("GLM_PLAN_PREFILL_SPLIT", forced, dw.make_plan)
+        _check(dw.prefill(plan=plan), ref, what + " (plan)")
+        _check(dw.prefill(plan=None), ref, what + " (no plan)")
+        import paper_2511_01633_amd as glm
+        ws = torch.empty(glm.glm_attn_workspace_bytes(w.geom, w.B, w.sum_q, int(w.seq_lens.max())), dtype=torch.uint8, device="cuda")
+        _check(dw.prefill(plan=None, workspace=ws), ref, what + " (no plan, workspace)")
+    if all(q == 1 for q in q_lens):
+        wd = W.Workload("as_decode", w.geom, w.pool, w.q, w.block_tables, w.seq_lens, w.scale)
+        dd = gu.DeviceWorkload(wd)
+        _check(dd.decode(plan=dd.make_plan()), ref, what + " (decode, plan)")
+        _check(dd.decode(plan=None), ref, what + " (decode, no plan)")
+
+
 def _permuted(w, seed):
     """The same batch with its blocks at other physical ids (pool permuted, tables remapped)."""
     perm = np.random.default_rng(seed).permutation(w.geom.num_blocks)
