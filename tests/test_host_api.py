@@ -282,6 +282,84 @@ def test_mixed_plan_with_chunked_prefill_rows_covers_everything_once():
     assert plan.workspace_bytes == w.sum_q * stride * w.geom.num_q_heads * (128 + 2) * 4
 
 
+def _plan_cover(w, plan):
+    """How often every (request, new token, q head, visible block) is covered by the entries of a plan of either
+    kind; a decode plan's token index is 0."""
+    G = w.geom.group
+    Hkv = w.geom.num_kv_heads
+    members = plan.members()
+    prefill = w.q_lens is not None
+    seen = {}
+    for c in plan.chunks():
+        if c.n_mem == 0:
+            continue
+        tile = 128 if c.waves == 4 else 16
+        heads = [c.kvh] if c.kvh >= 0 else list(range(Hkv))
+        assert (c.kvh >= 0) == (c.waves == 4)
+        if prefill and c.waves == 4:                       # a row tile of rep's new tokens
+            r = c.rep
+            ctx = int(w.seq_lens[r] - w.q_lens[r])
+            assert c.n_mem == w.q_lens[r] and w.q_lens[r] != 1
+            rows = [(r, rho // G, rho % G, ctx + rho // G + 1) for rho in range(c.row0, min(c.n_mem * G, c.row0 + tile))]
+        else:                                              # rows of member requests, one new token each
+            mem = members[c.mem_off:c.mem_off + c.n_mem]
+            rows = [(int(mem[rho // G]), 0, rho % G, int(w.seq_lens[int(mem[rho // G])]))
+                    for rho in range(c.row0, min(c.n_mem * G, c.row0 + tile))]
+            if prefill:
+                assert all(w.q_lens[r] == 1 for r, _, _, _ in rows)
+        for r, mi, gh, limit in rows:
+            nb = -(-limit // 16)
+            end = nb if c.b1 == 2 ** 31 - 1 else min(c.b1, nb)
+            for b in range(c.b0, end):
+                assert w.block_tables[r, b] == w.block_tables[c.rep, b]
+                for kvh in heads:
+                    key = (r, mi, kvh * G + gh, b)
+                    seen[key] = seen.get(key, 0) + 1
+    want = 0
+    for r in range(w.B):
+        n_new = 1 if not prefill else int(w.q_lens[r])
+        ctx = int(w.seq_lens[r]) - n_new
+        for mi in range(n_new):
+            want += -(-(ctx + mi + 1) // 16) * w.geom.num_q_heads if ctx + mi + 1 > 0 else 0
+    return seen, want
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_plans_cover_everything_once(seed, monkeypatch):
+    """Seeded random batches of every kind the planner distinguishes (decode; prefill with no, one or many new tokens
+    per request; shared prefix groups; long and short contexts; forced key chunks on odd seeds): every (request, new
+    token, q head, visible block) is covered by exactly one entry, and shared entries only group requests whose
+    tables agree on the blocks they walk."""
+    rng = np.random.default_rng(7000 + seed)
+    hkv = int(rng.choice([1, 2]))
+    hq = hkv * int(rng.choice([1, 2, 4]))
+    B = int(rng.integers(1, 9))
+    kind = rng.choice(["decode", "few", "mixed"])
+    groups, rest = [], list(range(B))
+    rng.shuffle(rest)
+    while len(rest) >= 2 and rng.random() < 0.7:
+        n = int(rng.integers(2, len(rest) + 1))
+        groups.append(sorted(rest[:n])); rest = rest[n:]
+    prefix_tokens = [int(rng.choice([16, 64, 400, 1104])) for _ in groups]
+    suffix = [int(rng.choice([0, 5, 300, 900])) for _ in range(B)]
+    if kind == "decode":
+        w = W.custom_decode(7100 + seed, prefix_groups=groups, prefix_tokens=prefix_tokens, suffix_tokens=suffix,
+                            num_q_heads=hq, num_kv_heads=hkv, head_dim=64)
+    else:
+        pick = [0, 2, 17, 60] if kind == "few" else [1, 1, 1, 0, 33, 70]
+        q_lens = [int(rng.choice(pick)) for _ in range(B)]
+        w = W.custom_prefill(7100 + seed, prefix_groups=groups, prefix_tokens=prefix_tokens, q_lens=q_lens,
+                             cached_suffix_tokens=suffix, num_q_heads=hq, num_kv_heads=hkv, head_dim=64)
+    if seed % 2:
+        monkeypatch.setenv("GLM_PLAN_PREFILL_SPLIT", str(int(rng.integers(2, 7))))
+        monkeypatch.setenv("GLM_PLAN_CHUNK_BLOCKS", str(int(rng.choice([2, 4, 8]))))
+        monkeypatch.setenv("GLM_PLAN_COOP_MIN_ROW_BLOCKS", "0")
+        monkeypatch.setenv("GLM_PLAN_COOP_MIN_ROWS", str(int(rng.choice([16, 32, 128]))))
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, w.q_lens, w.B)
+    seen, want = _plan_cover(w, plan)
+    assert len(seen) == want and set(seen.values()) <= {1}, (kind, len(seen), want)
+
+
 def test_plan_handles_partial_sharing_and_unequal_lengths():
     # request 1 ends inside the run shared with request 0; request 2 shares only the first block
     tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)
