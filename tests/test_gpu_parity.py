@@ -463,6 +463,20 @@ def test_seeded_random_batches_against_oracle(seed):
         dd = gu.DeviceWorkload(wd)
         _check(dd.decode(plan=dd.make_plan()), ref, what + " (decode, plan)")
         _check(dd.decode(plan=None), ref, what + " (decode, no plan)")
+        # the same batch planned with short chunks and shared runs of few rows on the cooperative kernel
+        knobs = {"GLM_PLAN_CHUNK_BLOCKS": str(int(rng.choice([2, 4, 8]))), "GLM_PLAN_COOP_CHUNK_BLOCKS": str(int(rng.choice([2, 6, 16]))),
+                 "GLM_PLAN_COOP_MIN_ROW_BLOCKS": "0", "GLM_PLAN_COOP_MIN_ROWS": str(int(rng.choice([2, 16, 48])))}
+        old = {k: os.environ.get(k) for k in knobs}
+        os.environ.update(knobs)
+        try:
+            odd = dd.make_plan()
+        finally:
+            for k, v in old.items():
+                if v is None:
+                    os.environ.pop(k, None)
+                else:
+                    os.environ[k] = v
+        _check(dd.decode(plan=odd), ref, what + " (decode, plan with %s)" % knobs)
 
 
 def _permuted(w, seed):
