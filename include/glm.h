@@ -208,7 +208,9 @@ GLM_API glm_plan *glm_plan_create_host(glm_geom g, const int32_t *block_tables_h
  */
 GLM_API int glm_plan_rebuild(glm_plan *plan, glm_geom g, const int32_t *block_tables_host, int32_t max_blocks,
                      const int32_t *seq_lens_host, const int32_t *q_lens_host, int32_t B, void *hip_stream);
+/* Frees a plan (NULL is allowed).  Waits for the device first: launches that read the plan may still be queued. */
 GLM_API void glm_plan_destroy(glm_plan *plan);
+/* Bytes of workspace a call with this plan needs (at least 256; the same for every layer that uses the plan). */
 GLM_API size_t glm_plan_workspace_bytes(const glm_plan *plan);
 
 /* One entry of a plan's work list, for inspection and tests. */
