@@ -474,7 +474,7 @@ def main():
         sys.exit(1)
     import paper_2511_01633_amd as glm
     import workloads as W
-    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3", "mixed", "short"}
+    only = set(x for x in args.only.split(",") if x) or {"decode8b", "prefill", "tree70b", "churn", "qwen3", "mixed", "short", "tiny"}
     torch.cuda.set_device(0)
     extra = {}
 
@@ -488,6 +488,10 @@ def main():
             extra["eviction_churn"] = bench_churn(glm, W, W.eviction_churn(), max(10, args.steps // 4), max(2, args.warmup // 4))
         if "mixed" in only:
             extra["mixed_batch"] = bench_mixed(glm, W.mixed_batch(), max(10, args.steps // 4), max(2, args.warmup // 4))
+        if "tiny" in only:
+            t = bench_decode(glm, W.tiny_decode(), 4, max(10, args.steps // 4), max(2, args.warmup // 4))
+            extra["tiny_decode"] = {k: t[k] for k in ("workload", "ms_per_step", "step_events", "ms_per_step_without_plan", "kernels",
+                                                        "unique_kv_bytes", "plan_build_ms", "plan_rebuild_ms")}
         if "short" in only:
             extra["short_turn_prefill"] = bench_short_turn(glm, W.short_turn_prefill(), max(10, args.steps // 4), max(2, args.warmup // 4))
             extra["mixed_short_turns"] = bench_short_turn(glm, W.mixed_short_turns(), max(10, args.steps // 4), max(2, args.warmup // 4))

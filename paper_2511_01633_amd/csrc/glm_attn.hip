@@ -609,12 +609,14 @@ __device__ __forceinline__ void attn_private_body(const AttnArgs &a, const glm_c
         c.mem_off = -1;
         c.n_mem = 1;
         c.row0 = rt * 16;
-        c.slot0 = (int)r * a.n_split + s;
+        c.slot0 = a.n_split > 1 ? (int)r * a.n_split + s : -1;     // a request in one piece writes its output itself
         c.ids_off = 0;
         c.n_ids = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) c.ids_head[i] = 0;
-        if ((int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;   // the merge never reads this slot
+        // a chunk beyond the request's end: the merge never reads its slot (an empty request in one piece goes on
+        // and writes its zeros)
+        if (c.slot0 >= 0 && (int64_t)c.b0 * kBlockSize >= a.seq_lens[r]) return;
     }
 
     // ---- addressing that needs nothing but the work item
@@ -1252,7 +1254,9 @@ int glm_attn_decode(glm_geom g, const void *kv_pool_dev, const void *q_dev, void
         m.n_split = a.n_split;
         m.chunk_blocks = a.chunk_blocks;
     }
-    if (e == hipSuccess) e = launch_merge(D, m, B * Hq, st);
+    // (nothing to merge when every request was streamed in one piece and wrote its output itself)
+    const bool need_merge = plan ? plan->needs_merge : a.n_split > 1;
+    if (e == hipSuccess && need_merge) e = launch_merge(D, m, B * Hq, st);
     return e == hipSuccess ? GLM_OK : set_hip_error(e);
 }
 

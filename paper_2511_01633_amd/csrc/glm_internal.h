@@ -68,6 +68,7 @@ struct glm_plan {
     std::vector<int32_t> members, block_ids, slot_ids, merge_kind, merge_cnt;
     int32_t merge_stride = 1;         // partial slots per request: request r owns slots r * stride .. + merge_cnt[r] - 1
     int32_t n_slots = 0;              // merge units * merge_stride (0 if nothing is merged); a slot holds Hq partial rows
+    bool needs_merge = true;          // decode plan: some request has partial results to combine (or is empty and gets zeros)
     bool merge_by_token = false;      // prefill plan with split-K: one merge unit per new token instead of per request
     int32_t n_shared_segments = 0;
     int64_t shared_blocks = 0;

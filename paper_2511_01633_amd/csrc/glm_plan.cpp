@@ -230,7 +230,19 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
     std::vector<char> planned(B, 0);
     for (int32_t r : all) planned[r] = 1;
     std::vector<Segment> segs;
-    if (!all.empty()) build_segments(tables, p.max_blocks, nblk, all, 0, segs);
+    // A batch of short sequences only (at most 14 blocks = 7 tiles each) is bound by launch latency, not by bytes:
+    // every request is then one uncut item that writes its output itself, and the call needs no merge launch
+    // (8 requests of up to 193 tokens, d = 64: 12.2 -> 8.5 us per step; from 15 blocks on two chunks and a merge
+    // are faster again: 11.8 against 13.0 us at d = 128).
+    int32_t longest = 0;
+    for (int32_t r : all) longest = std::max(longest, nblk[r]);
+    const bool tiny = !subset && !units && longest <= env_int("GLM_PLAN_TINY_BLOCKS", 14);
+    if (tiny) {
+        for (int32_t r : all)
+            if (nblk[r] > 0) segs.push_back({std::vector<int32_t>{r}, 0, nblk[r], true});
+    } else if (!all.empty()) {
+        build_segments(tables, p.max_blocks, nblk, all, 0, segs);
+    }
 
     // Segments with many rows go to the cooperative kernel (64 rows per workgroup share one staged
     // K/V tile); the rest is cut into wave-private items of 16 rows.
@@ -286,6 +298,7 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
         cb_single = clamp_cb(ns);
         if (count_items(cb_family, cb_single) <= target) break;
     }
+    if (tiny) cb_family = cb_single = std::max(cb_single, longest + (longest & 1));
     if (int forced = env_int("GLM_PLAN_CHUNK_BLOCKS", 0)) cb_family = cb_single = std::max(1, forced);
     // Cooperative runs are cut only as far as one round of the chip's 512 workgroup slots needs: every chunk
     // costs each member a partial result, and the slots a short round leaves empty are taken by the
@@ -400,6 +413,8 @@ int build_decode(glm_plan &p, const int32_t *tables, const int32_t *seq_lens, co
         else if (n_partials[r] == 0) p.merge_kind[u] = kMergeDirect;   // wrote its output itself
         else p.merge_kind[u] = kMergeList;
     }
+    p.needs_merge = false;
+    for (int32_t k : p.merge_kind) p.needs_merge |= k != kMergeDirect;
     std::vector<Work> quads = pack_quads(families, singles);
     p.chunks[0] = deal_to_xcds(quads, 4);
     if (!subset) p.chunks[1] = deal_to_xcds(coop, 1);
@@ -711,6 +726,7 @@ int glm_plan_rebuild(glm_plan *plan, glm_geom g, const int32_t *block_tables_hos
     plan->merge_stride = fresh->merge_stride;
     plan->n_slots = fresh->n_slots;
     plan->merge_by_token = fresh->merge_by_token;
+    plan->needs_merge = fresh->needs_merge;
     plan->n_shared_segments = fresh->n_shared_segments;
     plan->shared_blocks = fresh->shared_blocks;
     delete fresh;

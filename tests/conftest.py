@@ -8,6 +8,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# A decode batch whose sequences all fit 14 blocks is planned without any sharing or cutting (it is bound by launch
+# latency).  The tests exercise the sharing and split-K machinery at exactly such sizes, where the oracle is fast, so
+# they switch that shortcut off; the tests of the shortcut itself switch it back on.
+os.environ.setdefault("GLM_PLAN_TINY_BLOCKS", "0")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs an MI355X (run with -m gpu)")
 

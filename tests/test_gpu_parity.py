@@ -108,6 +108,9 @@ def _decode_both_ways(w, what, agree=1e-5):
 def test_decode_tiny_config():
     w = W.tiny_decode()
     _decode_both_ways(w, "tiny_decode")
+    # as planned by default: sequences this short are streamed in one piece each, no merge launch follows
+    _, plan, _, _ = _with_env("GLM_PLAN_TINY_BLOCKS", "14", lambda: _decode_both_ways(w, "tiny_decode, uncut"))
+    assert all(c.slot0 == -1 for c in plan.chunks() if c.n_mem)
 
 
 @pytest.mark.parametrize("hq,hkv,d", [(4, 4, 64), (8, 2, 128), (8, 1, 64), (32, 8, 128), (6, 2, 128), (40, 2, 64)])

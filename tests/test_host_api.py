@@ -360,6 +360,23 @@ def test_seeded_random_plans_cover_everything_once(seed, monkeypatch):
     assert len(seen) == want and set(seen.values()) <= {1}, (kind, len(seen), want)
 
 
+def test_tiny_batches_are_planned_uncut_and_unshared(monkeypatch):
+    """Sequences of at most 14 blocks: one uncut entry per request that writes its output itself, no partial results,
+    whatever the tables share; one block more and the batch is planned as usual."""
+    monkeypatch.setenv("GLM_PLAN_TINY_BLOCKS", "14")
+    w = W.tiny_decode()
+    plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
+    ch = [c for c in plan.chunks() if c.n_mem]
+    assert len(ch) == w.B and all(c.n_mem == 1 and c.slot0 == -1 and c.b0 == 0 and c.b1 == 2 ** 31 - 1 and c.waves == 1 for c in ch)
+    assert sorted(c.rep for c in ch) == list(range(w.B)) and plan.num_shared_segments == 0
+    seen, want = _plan_cover(w, plan)
+    assert len(seen) == want and set(seen.values()) == {1}
+    wl = W.custom_decode(61, prefix_groups=[[0, 1, 2]], prefix_tokens=[128], suffix_tokens=[10, 100, 3], num_q_heads=4,
+                         num_kv_heads=2, head_dim=64)                 # request 1: 128 + 100 + 1 tokens = 15 blocks
+    pl = glm.glm_plan_create_host(wl.geom, wl.block_tables, wl.max_blocks, wl.seq_lens, None, wl.B)
+    assert pl.num_shared_segments == 1
+
+
 def test_plan_handles_partial_sharing_and_unequal_lengths():
     # request 1 ends inside the run shared with request 0; request 2 shares only the first block
     tables = np.array([[5, 6, 7, 8], [5, 6, 7, -1], [5, 9, -1, -1], [3, -1, -1, -1]], np.int32)
