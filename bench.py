@@ -9,8 +9,11 @@ L2 or the Infinity Cache.  A step is one pass of the hot path over the batch: th
 (built once, reported separately), the streaming kernels and the split-K merge.
 
 `extra` carries the other rows of the path: prefill on a cached prefix (TFLOP/s on the exact
-causal flop count), the 70B-shaped prefix-tree decode, and an eviction-churn step
-(fork copy-on-write + gather out + gather in + decode).
+causal flop count), the 70B-shaped prefix-tree decode, an eviction-churn step (fork
+copy-on-write + gather out + gather in + decode), a mixed batch of prefills and decode steps,
+short turns on long cached contexts (alone and in the middle of a decode batch), a decode batch
+at the served model's attention shape, the tiny correctness configuration, the token gather and
+the block manager's hit rates.
 """
 from __future__ import annotations
 
@@ -35,7 +38,7 @@ def _parse():
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--layers", type=int, default=32, help="distinct KV pool copies the decode steps rotate over")
-    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3,mixed (default all)")
+    ap.add_argument("--only", default="", help="comma list of: decode8b,prefill,tree70b,churn,qwen3,mixed,short,tiny (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-headline", action="store_true",
                     help="profiling aid: run only the workloads named by --only and print their records")
