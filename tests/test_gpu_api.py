@@ -343,6 +343,50 @@ def test_kv_gather_tokens_bit_exact():
                                     0, 0, dst) == 0
 
 
+def test_calls_from_several_host_threads_on_their_own_streams():
+    """The serving layer runs one host thread per query: four threads issue decode and prefill calls at the same time,
+    each on a stream, an output and a workspace of its own, sharing the pool, the tables and the plans.  Every result
+    equals the single-threaded one bit for bit."""
+    import threading
+    gu = _gu()
+    import paper_2511_01633_amd as glm
+    w = W.custom_decode(5300, prefix_groups=[list(range(12))], prefix_tokens=[640], suffix_tokens=[int(x) for x in range(5, 500, 45)] + [3],
+                        num_q_heads=8, num_kv_heads=2, head_dim=128)
+    wp = W.custom_prefill(5301, prefix_groups=[[0, 1]], prefix_tokens=[1504], q_lens=[150, 9], cached_suffix_tokens=[37, 900],
+                          num_q_heads=8, num_kv_heads=2, head_dim=128)
+    dw, dp = gu.DeviceWorkload(w), gu.DeviceWorkload(wp)
+    plan, pplan = dw.make_plan(), dp.make_plan()
+    ref_d, ref_p = dw.decode(plan=plan), dp.prefill(plan=pplan)
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            st = torch.cuda.Stream()
+            out_d = torch.empty_like(dw.out); out_p = torch.empty_like(dp.out)
+            ws_d = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+            ws_p = torch.empty(pplan.workspace_bytes, dtype=torch.uint8, device="cuda")
+            for _ in range(20):
+                glm.glm_attn_decode(w.geom, dw.pool, dw.q, out_d, dw.tables, w.max_blocks, dw.seq_lens, w.B, w.scale, plan, ws_d,
+                                    hip_stream=st)
+                glm.glm_attn_prefill_on_prefix(wp.geom, dp.pool, dp.q, out_p, dp.tables, wp.max_blocks, dp.seq_lens, dp.cu, wp.B,
+                                               wp.sum_q, 150, wp.scale, pplan, ws_p, hip_stream=st)
+            st.synchronize()
+            results[k] = (out_d.cpu().numpy().astype(np.float64), out_p.cpu().numpy().astype(np.float64))
+        except Exception as e:      # noqa: BLE001
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors, errors
+    assert len(results) == 4
+    for k in range(4):
+        np.testing.assert_array_equal(results[k][0], ref_d)
+        np.testing.assert_array_equal(results[k][1], ref_p)
+
+
 def test_hot_calls_can_be_captured_in_a_graph():
     """The hot calls allocate nothing and record no memset: a captured decode step (streaming launch + merge) replays
     to the eager result, with eager work of the program between the replays."""
