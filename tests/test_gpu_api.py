@@ -415,3 +415,31 @@ def test_hot_calls_can_be_captured_in_a_graph():
         torch.cuda.synchronize()
         np.testing.assert_array_equal(out.cpu().numpy().astype(np.float64), eager)
         assert bool(torch.isfinite(scratch))
+    # the same for a mixed prefill call whose prefill rows are cut into chunks (fused launch + merge over the tokens)
+    wp = W.custom_prefill(9101, prefix_groups=[list(range(6))], prefix_tokens=[1536], q_lens=[1, 90, 1, 37, 1, 1],
+                          cached_suffix_tokens=[300, 2000, 5, 17, 40, 1200], num_q_heads=8, num_kv_heads=2, head_dim=128)
+    dp = gu.DeviceWorkload(wp)
+    pplan = dp.make_plan()
+    assert any(c.waves == 4 and c.slot0 >= 0 for c in pplan.chunks()) and any(c.waves == 1 and c.n_mem for c in pplan.chunks())
+    eager_p = dp.prefill(plan=pplan)
+    pws = torch.empty(pplan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    pout = torch.zeros_like(dp.out)
+
+    def pcall():
+        glm.glm_attn_prefill_on_prefix(wp.geom, dp.pool, dp.q, pout, dp.tables, wp.max_blocks, dp.seq_lens, dp.cu, wp.B, wp.sum_q,
+                                       90, wp.scale, pplan, pws)
+    pgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        pcall()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(pgraph, stream=side):
+            pcall()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        pout.fill_(float("nan"))
+        scratch = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        pgraph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(pout.cpu().numpy().astype(np.float64), eager_p)
+        assert bool(torch.isfinite(scratch))
