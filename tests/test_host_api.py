@@ -146,6 +146,36 @@ def test_cooperative_work_is_spread_over_all_xcds():
     assert min(per_xcd) == max(per_xcd) == 1024 * 4 // 128, per_xcd          # one kv head's row tiles per XCD
 
 
+def test_headers_are_plain_c_and_link_against_the_library(tmp_path):
+    """The boundary is a C ABI: both headers compile as strict C99, and a C program that calls through them links
+    against the built library and runs (host-only entry points: no GPU needed)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_glm.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "glm.h"\n#include "glm_cache.h"\n'
+        "int main(void) {\n"
+        "    glm_geom g = {64, 16, 2, 8, 128};\n"
+        "    int32_t tables[2 * 4] = {0, 1, 2, 3, 0, 1, 4, 5}, lens[2] = {60, 50};\n"
+        "    int st = -100;\n"
+        "    glm_plan *p = glm_plan_create_host(g, tables, 4, lens, NULL, 2, &st);\n"
+        "    if (!p || st != GLM_OK) return 1;\n"
+        '    printf("%d %d %s\\n", glm_version(), (int)glm_plan_num_shared_segments(p), glm_status_string(GLM_ERR_WORKSPACE));\n'
+        "    glm_plan_destroy(p);\n"
+        "    return 0;\n}\n")
+    exe = tmp_path / "use_glm"
+    lib_dir = os.path.dirname(glm.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"), str(src),
+                    "-o", str(exe), "-L", lib_dir, "-l:" + os.path.basename(glm.LIB_PATH), "-Wl,-rpath," + lib_dir],
+                   check=True, capture_output=True)
+    run = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    version, shared, msg = run.stdout.split(" ", 2)
+    assert int(version) == glm.glm_version() and int(shared) == 1 and "workspace" in msg
+
+
 def test_plan_rebuild_rejects_host_only_plans():
     w = W.tiny_decode()
     plan = glm.glm_plan_create_host(w.geom, w.block_tables, w.max_blocks, w.seq_lens, None, w.B)
