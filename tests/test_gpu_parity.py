@@ -331,6 +331,16 @@ def test_prefill_without_plan_cuts_keys_given_a_workspace(case):
     got1, n1 = _merge_launches(lambda: dw.prefill(plan=None, workspace=torch.empty(w.sum_q * slot, dtype=torch.uint8, device="cuda")))
     assert n1 == 0
     np.testing.assert_array_equal(got1, dw.prefill(plan=None))
+    # tables three times as wide as any request needs (unused entries -1): the chunks are cut from the width, so most of
+    # them lie behind every sequence and must leave nothing that a token merges
+    wide = np.full((w.B, 3 * w.max_blocks), -1, np.int32)
+    wide[:, :w.max_blocks] = w.block_tables
+    ww = W.Workload("wide_tables", w.geom, w.pool, w.q, wide, w.seq_lens, w.scale, q_lens=w.q_lens, cu_q_lens=w.cu_q_lens)
+    dww = gu.DeviceWorkload(ww)
+    wsw = torch.empty(glm.glm_attn_workspace_bytes(w.geom, w.B, w.sum_q, 3 * w.max_blocks * 16), dtype=torch.uint8, device="cuda")
+    gotw, nw = _merge_launches(lambda: dww.prefill(plan=None, workspace=wsw))
+    assert nw == 1
+    _check(gotw, ref, "plan-less chunked prefill, wide tables, shape %d" % case)
 
 
 def test_prefill_without_any_cached_prefix_and_row_vs_decode():
